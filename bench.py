@@ -1,0 +1,240 @@
+#!/usr/bin/env python3
+"""Benchmark of the Pipe-SGD aggregation + update path on one MI355X.
+
+One "step" = one iteration of the whole hot path over one batch of synthetic
+gradients already resident in HBM: the ring AllReduce of p = 4 simulated
+workers (first send, p-1 transmit-and-reduce rounds with decompress-sum-
+compress, p-1 send-back rounds, every hop's payload written to memory) and the
+staleness-1 momentum-SGD update of all p model replicas.
+
+Prints ONE JSON line.  `value` is algorithmic GB/s: the bytes the method moves
+per iteration (every hop's payload written once and read once, every replica's
+slot/w/v read and w/v written once) divided by the measured time.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+
+MODE_OF_CONFIG = {1: 0, 2: 0, 3: 1, 4: 2, 5: 1}
+
+
+def payload_bytes_per_elem(mode: int) -> float:
+    return {0: 4.0, 1: 2.0, 2: 1.0 + 4.0 / 4096.0}[mode]
+
+
+def bytes_model(mode: int, n: int, p: int, momentum: bool):
+    """Algorithmic bytes of one iteration, by phase (stepwise schedule)."""
+    cb = payload_bytes_per_elem(mode)
+    first = 0.0 if mode == 0 else (4.0 + cb) * n
+    rs = (p - 1) * n * (cb + 4.0 + cb)
+    ag = (p - 1) * n * 2.0 * cb
+    upd = p * n * (cb + (16.0 if momentum else 8.0))
+    return {"first_send": first, "reduce_scatter": rs, "allgather": ag, "update": upd,
+            "total": first + rs + ag + upd}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=3, help="workload 1..5 (3 = AlexNet-shaped, 61M, the headline)")
+    ap.add_argument("--mode", type=int, default=None, help="override compression mode 0/1/2")
+    ap.add_argument("--schedule", choices=["stepwise", "fused"], default="stepwise")
+    ap.add_argument("--workers", type=int, default=4)
+    ap.add_argument("--lr", type=float, default=0.01)
+    ap.add_argument("--momentum", type=float, default=None)
+    ap.add_argument("--seed", type=int, default=1)
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle timing (0 = skip)")
+    ap.add_argument("--phases", action="store_true", help="also time each phase separately")
+    args = ap.parse_args()
+
+    if args.gpus != 1:
+        print("bench.py: this build runs the K simulated workers on ONE GPU; --gpus must be 1 "
+              "(no multi-GPU path exists in this repository)", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_1811_03619_amd import binding as B
+    from paper_1811_03619_amd import workloads as W
+    from paper_1811_03619_amd.pipeline import PipeSgdSim
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+
+    cfg, p = args.config, args.workers
+    mode = MODE_OF_CONFIG[cfg] if args.mode is None else args.mode
+    momentum = (0.0 if cfg == 1 else 0.9) if args.momentum is None else args.momentum
+    schedule = B.STEPWISE if args.schedule == "stepwise" else B.FUSED
+
+    specs = W.config_tensors(cfg)
+    numels = [s.numel for s in specs]
+    buckets = None
+    if cfg == 5:
+        buckets, offs, n = B.bucket_plan(numels, 1 << 20)
+    else:
+        offs, n = list(np.cumsum([0] + numels[:-1])), int(sum(numels))
+
+    def host_gradient(r: int) -> np.ndarray:
+        flat = np.zeros(n, dtype=np.float32)
+        for t, o in zip(W.gradient_tensors(cfg, r, args.seed), offs):
+            flat[o:o + t.size] = t
+        return flat
+
+    t0 = time.time()
+    grads = [host_gradient(r) for r in range(p)]
+    w0 = W.gaussian(n, 0.05, args.seed, (cfg, 99, 0, 0))
+    gen_s = time.time() - t0
+
+    sim = PipeSgdSim(mode, p, n, args.lr, momentum, 1.0, 2, buckets, schedule)
+    sim.set_gradients(grads)
+    sim.set_model(w0)
+    torch.cuda.synchronize()
+
+    for _ in range(args.warmup):
+        sim.iteration()
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly `steps` iterations; the update launch of every
+    # iteration is bracketed by events on the launch stream for the roofline.
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    start_ev, stop_ev = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t_begin = time.perf_counter()
+    start_ev.record()
+    for i in range(args.steps):
+        cur = sim.allreduce()
+        ev[i][0].record()
+        sim.update_from(1 - cur)
+        ev[i][1].record()
+        sim.t += 1
+    stop_ev.record()
+    torch.cuda.synchronize()
+    wall_s = time.perf_counter() - t_begin
+    ms_per_step = wall_s * 1e3 / args.steps
+    gpu_ms_per_step = start_ev.elapsed_time(stop_ev) / args.steps
+    upd_ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+
+    model = bytes_model(mode, n, p, momentum != 0.0)
+    value = model["total"] / (ms_per_step * 1e-3) / 1e9
+    upd_gbs = model["update"] / (upd_ms * 1e-3) / 1e9
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "update_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            rec = json.load(open(tpath))
+            key = f"config{cfg}_mode{mode}"
+            if key in rec:
+                traffic = rec[key]
+        except Exception:
+            traffic = None
+
+    out = {
+        "metric": "aggregation+update GB/s (fraction of HBM peak) and iters/s at K=4, 61M params",
+        "value": round(value, 2),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": f"config{cfg}:{W.CONFIG_NAMES[cfg]}", "workers": p, "elements_per_worker": n,
+            "tensors": len(specs), "buckets": len(buckets) if buckets else 1,
+            "compression": ["none", "trunc16", "quant8"][mode], "momentum": momentum, "lr": args.lr,
+            "pipeline_width": 2, "schedule": args.schedule, "seed": args.seed,
+        },
+        "iters_per_s": round(1e3 / ms_per_step, 2),
+        "hbm_peak_fraction": round(value / HBM_PEAK_GBS, 4),
+        "gpu_ms_per_step": round(gpu_ms_per_step, 5),
+        "bytes_per_iter": {k: int(v) for k, v in model.items()},
+        "roofline": {
+            "kernel": "update_kernel (decompress + momentum-SGD, all replicas, one launch)",
+            "bound": "hbm", "achieved": round(upd_gbs, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": round(upd_gbs / HBM_PEAK_GBS, 4), "traffic": traffic,
+            "launch_ms": round(upd_ms, 5), "algorithmic_bytes_per_launch": int(model["update"]),
+        },
+        "input_generation_s": round(gen_s, 2),
+    }
+
+    if args.phases:
+        out["phases_ms"] = time_phases(sim, B, torch, np)
+
+    if args.cpu_seconds > 0:
+        out["cpu_baseline"] = cpu_baseline(mode, grads, w0, p, args.lr, momentum, buckets, model["total"],
+                                           args.cpu_seconds)
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+def time_phases(sim, B, torch, np, reps: int = 20):
+    """Per-launch durations of each phase (separate pass, after the timed region)."""
+    ring = sim.rings[0]
+    p = sim.p
+    res = {}
+
+    def timed(fn):
+        ts = []
+        for _ in range(reps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(); fn(); b.record()
+            torch.cuda.synchronize()
+            ts.append(a.elapsed_time(b))
+        return round(float(np.median(ts)), 5)
+
+    res["first_send"] = timed(lambda: B.ring_first_send(ring))
+    res["reduce_scatter_step"] = [timed(lambda s=s: B.ring_reduce_scatter_step(ring, s)) for s in range(p - 1)]
+    res["allgather_step"] = [timed(lambda s=s: B.ring_allgather_step(ring, s)) for s in range(p - 1)]
+    res["allreduce_stepwise"] = timed(lambda: B.allreduce_sim(ring, B.STEPWISE))
+    res["allreduce_fused"] = timed(lambda: B.allreduce_sim(ring, B.FUSED))
+    res["update_all_replicas"] = timed(lambda: sim.update_from(1))
+    return res
+
+
+def cpu_baseline(mode, grads, w0, p, lr, momentum, buckets, bytes_total, budget_s):
+    """The oracle as it stands, one host thread, same inputs, same iteration
+    (AllReduce of p workers + update of p replicas)."""
+    import numpy as np
+
+    import oracle
+    n = w0.size
+    ws = [w0.copy() for _ in range(p)]
+    vs = [np.zeros(n, np.float32) for _ in range(p)]
+    slot = None
+    iters, t0 = 0, time.perf_counter()
+    while True:
+        A = oracle.allreduce_bucketed(mode, grads, buckets) if buckets else oracle.allreduce(mode, grads)
+        use = A if slot is None else slot           # same work either way; first pass has no earlier slot
+        for r in range(p):
+            oracle.sgd_update(mode, use[r][0], use[r][1], ws[r], vs[r] if momentum else None, lr, momentum, 1.0)
+        slot = A
+        iters += 1
+        el = time.perf_counter() - t0
+        if el >= budget_s or (iters >= 1 and el * (iters + 1) / iters > 2.5 * budget_s):
+            break
+    s_per_iter = el / iters
+    return {"value": round(bytes_total / s_per_iter / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": f"{iters} full iteration(s) of the same workload (all {p} workers, all {n} elements)",
+            "s_per_iter": round(s_per_iter, 4), "iters_per_s": round(1.0 / s_per_iter, 4)}
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,219 @@
+/*
+ * libpipesgd -- the gradient aggregation + update path of Pipe-SGD
+ * (arXiv 1811.03619) for one AMD MI355X (gfx950), behind a C ABI.
+ *
+ * The p workers of the paper's cluster are simulated as p gradient buffers in
+ * one GPU's memory: this library runs every worker's share of the ring
+ * AllReduce (Sec. 3.1), the light lossy compression on every ring hop
+ * (Sec. 3.2) and the pipelined SGD update (Algorithm 1), as HIP kernels.
+ *
+ * Conventions common to every entry point
+ *   - Return value: 0 on success, a negative PIPESGD_ERR_* otherwise.  Nothing
+ *     throws, aborts or logs.  On error nothing has been enqueued.
+ *   - "DEVICE" pointers are HIP device memory owned by the caller; the library
+ *     allocates no device memory and keeps no state between calls.  "HOST"
+ *     pointers are ordinary host memory read during the call only.
+ *   - Every DEVICE pointer must be 16-byte aligned.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls enqueue work on it and return without synchronising.  Calls on
+ *     one stream execute in order; calls that touch the same buffers from
+ *     different streams must be ordered by the caller.
+ *   - Inputs declared const are never written; gradients are never modified.
+ *   - Inputs must be finite.  NaN or Inf in a quantised block is a caller
+ *     error and is not detected.
+ *
+ * Layout
+ *   A gradient is a flat fp32 vector of n elements.  It is split into p ring
+ *   blocks ("chunks") of pipesgd_chunk_elems(n, p) elements (the last ones
+ *   may be short or empty).  A compressed vector ("payload") uses the same
+ *   element index space: element i of the payload encodes element i of the
+ *   vector, so chunk c of a payload starts at element c * chunk_elems.
+ *     PIPESGD_NONE     payload = float[n]
+ *     PIPESGD_TRUNC16  payload = uint16_t[n]  (upper half of the fp32 pattern)
+ *     PIPESGD_QUANT8   payload = int8_t[n] plus scales = float[ceil(n/4096)],
+ *                      scales[b] belonging to elements [4096 b, 4096 b + 4096)
+ *   With bucketing, several vectors ("buckets") live in one packed buffer, each
+ *   starting at a multiple of 4096 elements; each bucket is ring-reduced as a
+ *   vector of its own with its own p chunks.  Padding between buckets must be
+ *   zero in the gradients and is never written in payloads.
+ */
+#ifndef PIPESGD_H
+#define PIPESGD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PIPESGD_VERSION      100      /* major*10000 + minor*100 + patch */
+#define PIPESGD_MAX_WORKERS  16
+#define PIPESGD_MAX_BUCKETS  64
+#define PIPESGD_QBLOCK       4096     /* elements per quantisation block and per tile */
+
+/* compression modes (Sec. 3.2; widths from Sec. 4 "Results and Analysis":
+ * 16-bit truncation "T", 8-bit quantisation "Q") */
+#define PIPESGD_NONE     0
+#define PIPESGD_TRUNC16  1
+#define PIPESGD_QUANT8   2
+
+/* schedules of pipesgd_allreduce_sim */
+#define PIPESGD_STEPWISE 0   /* one launch per ring round; every hop's payload is written to memory */
+#define PIPESGD_FUSED    1   /* one launch; hop payloads stay in registers; same result bits */
+
+#define PIPESGD_OK             0
+#define PIPESGD_ERR_ARG       -1   /* null pointer, count or index out of range */
+#define PIPESGD_ERR_ALIGN     -2   /* a DEVICE pointer is not 16-byte aligned, or a bucket start is not a multiple of 4096 */
+#define PIPESGD_ERR_MODE      -3   /* unknown compression mode or schedule */
+#define PIPESGD_ERR_CAPACITY  -4   /* more workers or buckets than the library supports, or output table too small */
+#define PIPESGD_ERR_HIP       -5   /* the HIP runtime refused the launch */
+
+const char *pipesgd_strerror(int err);
+int pipesgd_version(void);
+
+/* ------------------------------------------------------------------ sizes -- */
+
+/* Length of one ring block: ceil(n/p) rounded up to a multiple of 4096, so that
+ * no quantisation block straddles two ring blocks ("a block of the entire
+ * gradient vector", Sec. 3.1; n/p in Eq. 5).  0 if p < 1. */
+uint64_t pipesgd_chunk_elems(uint64_t n, int workers);
+/* Bytes of a payload of n elements, scales not included; 0 for a bad mode. */
+uint64_t pipesgd_payload_bytes(int mode, uint64_t n);
+/* Number of fp32 scales that go with a payload of n elements (0 unless QUANT8). */
+uint64_t pipesgd_num_scales(int mode, uint64_t n);
+
+/* ----------------------------------------------------------------- codecs -- */
+
+/* Compress(g) of Algorithm 1 (compute thread, line 9) / Sec. 3.2.
+ *   TRUNC16: keep sign, exponent and 7 leading mantissa bits (toward zero).
+ *   QUANT8 : per block of 4096 elements counted from src[0]: scale = max|x|;
+ *            inv = 127/scale (one fp32 division, saturated at FLT_MAX);
+ *            q = clamp(rint(x*inv), -127, 127), ties to even; scale 0 -> q 0.
+ *   NONE   : copy.
+ * src: DEVICE float[n].  payload: DEVICE, pipesgd_payload_bytes(mode,n) bytes.
+ * scales: DEVICE float[pipesgd_num_scales(mode,n)], ignored unless QUANT8.
+ * n may be 0 (nothing is enqueued).  src and payload must not overlap. */
+int pipesgd_compress(int mode, const float *src, uint64_t n, void *payload, float *scales, void *stream);
+
+/* Decompress(g^c) of Algorithm 1 (compute thread, line 4) / Sec. 3.2.
+ *   TRUNC16: the 16 kept bits followed by 16 zero bits.
+ *   QUANT8 : x = (float)q * (scale/127)  (one division per block, one multiply per element).
+ * dst: DEVICE float[n]. */
+int pipesgd_decompress(int mode, const void *payload, const float *scales, uint64_t n, float *dst, void *stream);
+
+/* ------------------------------------------------------------------- ring -- */
+
+typedef struct pipesgd_bucket {
+    uint64_t start;      /* first element in the packed buffer; multiple of 4096 */
+    uint64_t n;          /* elements */
+} pipesgd_bucket;
+
+/* One AllReduce over p simulated workers (Alg. 1, communication thread line 4:
+ * g^c_sum <- sum of g^c_local).  Plain data; the caller fills it. */
+typedef struct pipesgd_ring {
+    int32_t  workers;                 /* p, 1..PIPESGD_MAX_WORKERS */
+    int32_t  mode;                    /* PIPESGD_NONE / TRUNC16 / QUANT8 */
+    uint64_t n;                       /* elements of each worker's (packed) vector */
+    uint32_t num_buckets;             /* 0: the whole vector is one bucket {0, n} */
+    uint32_t reserved;                /* must be 0 */
+    const pipesgd_bucket *buckets;    /* HOST, num_buckets entries, ascending, non-overlapping */
+    const float *g_local[PIPESGD_MAX_WORKERS];  /* DEVICE float[n]: worker r's local gradient */
+    void        *g_sum_c[PIPESGD_MAX_WORKERS];  /* DEVICE payload of n elements: worker r's result
+                                                   slot; also holds the hop payloads worker r sends
+                                                   while the AllReduce is in progress */
+    float       *scales[PIPESGD_MAX_WORKERS];   /* DEVICE float[num_scales]; QUANT8 only */
+} pipesgd_ring;
+
+/* Ring convention (the paper's Fig. 2(c) fixes none): worker r sends to worker
+ * (r+1) mod p.  Chunk c starts its sum on worker c:
+ *     P_0 = g_c[c];   P_j = D(C(P_{j-1})) + g_{(c+j) mod p}[c],  j = 1..p-1,
+ * the local operand always in full fp32 precision, one IEEE add per element.
+ * After the p-1 transmit-and-reduce rounds worker r owns chunk (r+1) mod p. */
+
+/* Worker r compresses the chunk it sends in round 0 (chunk r) into its slot:
+ * g_sum_c[r][chunk r] = C(g_local[r][chunk r]), all r in one launch.
+ * With PIPESGD_NONE and p > 1 nothing is enqueued (round 0 then reads the
+ * sender's gradient itself); with p == 1 this produces the whole result. */
+int pipesgd_ring_first_send(const pipesgd_ring *ring, void *stream);
+
+/* Transmit-and-reduce round `step` (0 <= step <= p-2) for all p workers in one
+ * launch (Sec. 3.1; with compression: decompress, sum, compress -- Sec. 3.2):
+ * worker r reads chunk j = (r-step-1) mod p from worker (r-1)'s slot, adds its
+ * own g_local chunk j and writes C(sum) to chunk j of its own slot.  After
+ * round p-2 worker r's slot holds the final C(P_{p-1}) of chunk (r+1) mod p.
+ * Rounds must be enqueued in order after pipesgd_ring_first_send. */
+int pipesgd_ring_reduce_scatter_step(const pipesgd_ring *ring, int step, void *stream);
+
+/* Send-back round `step` (0 <= step <= p-2) for all p workers in one launch
+ * (Sec. 3.1: the reduced blocks are sent on round the ring): worker r copies
+ * chunk (r-step) mod p, payload bytes and scales verbatim, from worker (r-1)'s
+ * slot into its own.  After round p-2 all p slots hold identical bytes. */
+int pipesgd_ring_allgather_step(const pipesgd_ring *ring, int step, void *stream);
+
+/* The whole AllReduce: first_send, p-1 reduce-scatter rounds, p-1 all-gather
+ * rounds.  PIPESGD_STEPWISE enqueues exactly those launches.  PIPESGD_FUSED
+ * enqueues one kernel that walks each chunk's chain in registers and writes
+ * only the final payload to all p slots: same bits in g_sum_c/scales, fewer
+ * bytes moved, for launch-bound (small or many-bucket) gradients. */
+int pipesgd_allreduce_sim(const pipesgd_ring *ring, int schedule, void *stream);
+
+/* ----------------------------------------------------------------- update -- */
+
+/* Algorithm 1, compute thread lines 4-5, on one model replica:
+ *     g = D(g_sum_c);  if grad_scale != 1: g = g * grad_scale;
+ *     momentum != 0:  v = fma(momentum, v, g);  w = fma(-lr, v, w)
+ *     momentum == 0:  w = fma(-lr, g, w)                (v may be NULL, untouched)
+ * The pipelined method (width 2, staleness 1 -- Sec. 3.1) passes the result
+ * slot of the PREVIOUS iteration's AllReduce; an all-zero slot (the initial
+ * state of Alg. 1, communication thread line 1) leaves w unchanged.  Passing
+ * the current iteration's slot gives decentralised synchronous SGD.
+ * g_sum_c / scales: DEVICE payload of n elements.  w, v: DEVICE float[n]. */
+int pipesgd_apply_update(int mode, const void *g_sum_c, const float *scales, uint64_t n,
+                         float *w, float *v, float lr, float momentum, float grad_scale,
+                         void *stream);
+
+/* The same update on `replicas` model replicas (one per simulated worker) in a
+ * single launch.  The four arrays are HOST arrays of DEVICE pointers;
+ * v may be NULL iff momentum == 0. */
+int pipesgd_apply_update_multi(int mode, int replicas, const void *const *g_sum_c,
+                               const float *const *scales, uint64_t n, float *const *w,
+                               float *const *v, float lr, float momentum, float grad_scale,
+                               void *stream);
+
+/* -------------------------------------------------------------- bucketing -- */
+
+/* Small-tensor fusion (not in the paper, which sends the gradient as one
+ * segment -- L = 1 in Eq. 6): tensors in declaration order are packed greedily;
+ * a bucket is closed when the next tensor would take it past bucket_elems; a
+ * larger tensor gets a bucket of its own; every bucket starts at a multiple of
+ * 4096 elements.  All arguments HOST.  Writes tensor_offsets[num_tensors]
+ * (packed-buffer element offset of each tensor), up to max_buckets buckets and
+ * *n_packed (packed length, multiple of 4096).  Returns the number of buckets,
+ * or PIPESGD_ERR_CAPACITY if max_buckets is too small (nothing useful written). */
+int pipesgd_bucket_plan(const uint64_t *numels, uint64_t num_tensors, uint64_t bucket_elems,
+                        pipesgd_bucket *buckets, uint64_t max_buckets,
+                        uint64_t *tensor_offsets, uint64_t *n_packed);
+
+/* One tensor <-> packed-buffer copy.  32 bytes. */
+typedef struct pipesgd_segment {
+    float   *tensor;      /* DEVICE float[numel], 4-byte aligned is enough */
+    float   *packed;      /* DEVICE: where the tensor lives in a packed buffer */
+    uint64_t numel;
+    uint64_t first_tile;  /* filled by pipesgd_segments_prepare */
+} pipesgd_segment;
+
+/* HOST: fills first_tile of each of the num segments (prefix sum of
+ * ceil(numel/4096)) and returns the total tile count in *total_tiles.  The
+ * caller then copies the table to the device. */
+int pipesgd_segments_prepare(pipesgd_segment *segments, uint64_t num, uint64_t *total_tiles);
+
+/* Gather (tensor -> packed) / scatter (packed -> tensor) all segments in one
+ * launch.  segments: DEVICE table of num entries prepared as above. */
+int pipesgd_pack(const pipesgd_segment *segments, uint64_t num, uint64_t total_tiles, void *stream);
+int pipesgd_unpack(const pipesgd_segment *segments, uint64_t num, uint64_t total_tiles, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PIPESGD_H */

@@ -1,0 +1,271 @@
+"""ctypes binding of ``libpipesgd.so``: same names as the C ABI
+(``include/pipesgd.h``), argument marshalling only.  Device memory and streams
+come from PyTorch; every computation runs in the library's HIP kernels.
+
+There is no fallback: if the library cannot be loaded, or a call fails, a
+``PipeSgdError`` is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence, Tuple
+
+from . import buildlib
+
+NONE, TRUNC16, QUANT8 = 0, 1, 2
+STEPWISE, FUSED = 0, 1
+MAX_WORKERS = 16
+MAX_BUCKETS = 64
+QBLOCK = 4096
+
+EXPORTS = [
+    "pipesgd_strerror", "pipesgd_version", "pipesgd_chunk_elems", "pipesgd_payload_bytes",
+    "pipesgd_num_scales", "pipesgd_compress", "pipesgd_decompress", "pipesgd_ring_first_send",
+    "pipesgd_ring_reduce_scatter_step", "pipesgd_ring_allgather_step", "pipesgd_allreduce_sim",
+    "pipesgd_apply_update", "pipesgd_apply_update_multi", "pipesgd_bucket_plan",
+    "pipesgd_segments_prepare", "pipesgd_pack", "pipesgd_unpack",
+]
+
+
+class PipeSgdError(RuntimeError):
+    pass
+
+
+class Bucket(C.Structure):
+    _fields_ = [("start", C.c_uint64), ("n", C.c_uint64)]
+
+
+class RingStruct(C.Structure):
+    _fields_ = [
+        ("workers", C.c_int32),
+        ("mode", C.c_int32),
+        ("n", C.c_uint64),
+        ("num_buckets", C.c_uint32),
+        ("reserved", C.c_uint32),
+        ("buckets", C.POINTER(Bucket)),
+        ("g_local", C.c_void_p * MAX_WORKERS),
+        ("g_sum_c", C.c_void_p * MAX_WORKERS),
+        ("scales", C.c_void_p * MAX_WORKERS),
+    ]
+
+
+class Segment(C.Structure):
+    _fields_ = [("tensor", C.c_void_p), ("packed", C.c_void_p), ("numel", C.c_uint64),
+                ("first_tile", C.c_uint64)]
+
+
+_lib = None
+
+
+def lib():
+    """Open libpipesgd.so (building it first only if no built library exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = buildlib.LIB_PATH
+    if not os.path.exists(path):
+        buildlib.build(force=True)
+    try:
+        L = C.CDLL(path)
+    except OSError as e:                                    # pragma: no cover
+        raise PipeSgdError(f"cannot load {path}: {e}") from e
+    vp, u64, i32, f32 = C.c_void_p, C.c_uint64, C.c_int, C.c_float
+    L.pipesgd_strerror.restype = C.c_char_p
+    L.pipesgd_strerror.argtypes = [i32]
+    L.pipesgd_version.restype = i32
+    L.pipesgd_version.argtypes = []
+    L.pipesgd_chunk_elems.restype = u64
+    L.pipesgd_chunk_elems.argtypes = [u64, i32]
+    L.pipesgd_payload_bytes.restype = u64
+    L.pipesgd_payload_bytes.argtypes = [i32, u64]
+    L.pipesgd_num_scales.restype = u64
+    L.pipesgd_num_scales.argtypes = [i32, u64]
+    L.pipesgd_compress.restype = i32
+    L.pipesgd_compress.argtypes = [i32, vp, u64, vp, vp, vp]
+    L.pipesgd_decompress.restype = i32
+    L.pipesgd_decompress.argtypes = [i32, vp, vp, u64, vp, vp]
+    L.pipesgd_ring_first_send.restype = i32
+    L.pipesgd_ring_first_send.argtypes = [C.POINTER(RingStruct), vp]
+    L.pipesgd_ring_reduce_scatter_step.restype = i32
+    L.pipesgd_ring_reduce_scatter_step.argtypes = [C.POINTER(RingStruct), i32, vp]
+    L.pipesgd_ring_allgather_step.restype = i32
+    L.pipesgd_ring_allgather_step.argtypes = [C.POINTER(RingStruct), i32, vp]
+    L.pipesgd_allreduce_sim.restype = i32
+    L.pipesgd_allreduce_sim.argtypes = [C.POINTER(RingStruct), i32, vp]
+    L.pipesgd_apply_update.restype = i32
+    L.pipesgd_apply_update.argtypes = [i32, vp, vp, u64, vp, vp, f32, f32, f32, vp]
+    L.pipesgd_apply_update_multi.restype = i32
+    L.pipesgd_apply_update_multi.argtypes = [i32, i32, vp, vp, u64, vp, vp, f32, f32, f32, vp]
+    L.pipesgd_bucket_plan.restype = i32
+    L.pipesgd_bucket_plan.argtypes = [C.POINTER(u64), u64, u64, C.POINTER(Bucket), u64,
+                                      C.POINTER(u64), C.POINTER(u64)]
+    L.pipesgd_segments_prepare.restype = i32
+    L.pipesgd_segments_prepare.argtypes = [C.POINTER(Segment), u64, C.POINTER(u64)]
+    L.pipesgd_pack.restype = i32
+    L.pipesgd_pack.argtypes = [vp, u64, u64, vp]
+    L.pipesgd_unpack.restype = i32
+    L.pipesgd_unpack.argtypes = [vp, u64, u64, vp]
+    _lib = L
+    return L
+
+
+def strerror(rc: int) -> str:
+    return lib().pipesgd_strerror(rc).decode()
+
+
+def check(rc: int, what: str = "pipesgd") -> None:
+    if rc != 0:
+        raise PipeSgdError(f"{what}: {strerror(rc)} ({rc})")
+
+
+# --------------------------------------------------------------- marshalling --
+
+def _ptr(t) -> Optional[int]:
+    """Device (or host) address of a torch tensor, or a raw int / None."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def _ptr_array(items: Sequence) -> C.Array:
+    arr = (C.c_void_p * len(items))()
+    for i, t in enumerate(items):
+        arr[i] = _ptr(t)
+    return arr
+
+
+def version() -> int:
+    return int(lib().pipesgd_version())
+
+
+def chunk_elems(n: int, workers: int) -> int:
+    return int(lib().pipesgd_chunk_elems(n, workers))
+
+
+def payload_bytes(mode: int, n: int) -> int:
+    return int(lib().pipesgd_payload_bytes(mode, n))
+
+
+def num_scales(mode: int, n: int) -> int:
+    return int(lib().pipesgd_num_scales(mode, n))
+
+
+def compress(mode: int, src, n: int, payload, scales=None, stream=None) -> None:
+    check(lib().pipesgd_compress(mode, _ptr(src), n, _ptr(payload), _ptr(scales), _stream(stream)),
+          "pipesgd_compress")
+
+
+def decompress(mode: int, payload, scales, n: int, dst, stream=None) -> None:
+    check(lib().pipesgd_decompress(mode, _ptr(payload), _ptr(scales), n, _ptr(dst), _stream(stream)),
+          "pipesgd_decompress")
+
+
+def make_ring(mode: int, n: int, g_local: Sequence, g_sum_c: Sequence, scales: Optional[Sequence] = None,
+              buckets: Optional[Sequence[Tuple[int, int]]] = None) -> RingStruct:
+    """Fill a pipesgd_ring.  The returned struct keeps the bucket table alive."""
+    p = len(g_local)
+    if p > MAX_WORKERS:
+        raise PipeSgdError("too many workers")
+    R = RingStruct()
+    R.workers, R.mode, R.n, R.reserved = p, mode, n, 0
+    if buckets:
+        tab = (Bucket * len(buckets))(*[Bucket(int(s), int(m)) for s, m in buckets])
+        R._bucket_keepalive = tab
+        R.buckets = C.cast(tab, C.POINTER(Bucket))
+        R.num_buckets = len(buckets)
+    else:
+        R.num_buckets = 0
+        R.buckets = None
+    for r in range(p):
+        R.g_local[r] = _ptr(g_local[r])
+        R.g_sum_c[r] = _ptr(g_sum_c[r])
+        R.scales[r] = _ptr(scales[r]) if scales is not None else None
+    return R
+
+
+def ring_first_send(ring: RingStruct, stream=None) -> None:
+    check(lib().pipesgd_ring_first_send(C.byref(ring), _stream(stream)), "pipesgd_ring_first_send")
+
+
+def ring_reduce_scatter_step(ring: RingStruct, step: int, stream=None) -> None:
+    check(lib().pipesgd_ring_reduce_scatter_step(C.byref(ring), step, _stream(stream)),
+          "pipesgd_ring_reduce_scatter_step")
+
+
+def ring_allgather_step(ring: RingStruct, step: int, stream=None) -> None:
+    check(lib().pipesgd_ring_allgather_step(C.byref(ring), step, _stream(stream)),
+          "pipesgd_ring_allgather_step")
+
+
+def allreduce_sim(ring: RingStruct, schedule: int = STEPWISE, stream=None) -> None:
+    check(lib().pipesgd_allreduce_sim(C.byref(ring), schedule, _stream(stream)), "pipesgd_allreduce_sim")
+
+
+def apply_update(mode: int, g_sum_c, scales, n: int, w, v, lr: float, momentum: float = 0.0,
+                 grad_scale: float = 1.0, stream=None) -> None:
+    check(lib().pipesgd_apply_update(mode, _ptr(g_sum_c), _ptr(scales), n, _ptr(w), _ptr(v),
+                                     lr, momentum, grad_scale, _stream(stream)), "pipesgd_apply_update")
+
+
+class UpdateArgs:
+    """Pre-marshalled pointer tables for pipesgd_apply_update_multi, so that a
+    timed loop does not rebuild them on every call."""
+
+    def __init__(self, g_sum_c: Sequence, scales: Optional[Sequence], w: Sequence, v: Optional[Sequence]):
+        self.replicas = len(w)
+        self.g_sum_c = _ptr_array(g_sum_c)
+        self.scales = _ptr_array(scales) if scales is not None else None
+        self.w = _ptr_array(w)
+        self.v = _ptr_array(v) if v is not None else None
+
+
+def apply_update_multi(mode: int, args: UpdateArgs, n: int, lr: float, momentum: float = 0.0,
+                       grad_scale: float = 1.0, stream=None) -> None:
+    check(lib().pipesgd_apply_update_multi(mode, args.replicas, args.g_sum_c, args.scales, n, args.w, args.v,
+                                           lr, momentum, grad_scale, _stream(stream)),
+          "pipesgd_apply_update_multi")
+
+
+def bucket_plan(numels: Sequence[int], bucket_elems: int = 1 << 20, max_buckets: int = MAX_BUCKETS):
+    """Host planner.  Returns (buckets [(start, n)], tensor_offsets, n_packed)."""
+    nt = len(numels)
+    arr = (C.c_uint64 * max(nt, 1))(*numels)
+    out_b = (Bucket * max_buckets)()
+    out_o = (C.c_uint64 * max(nt, 1))()
+    n_packed = C.c_uint64(0)
+    rc = lib().pipesgd_bucket_plan(arr, nt, bucket_elems, out_b, max_buckets, out_o, C.byref(n_packed))
+    if rc < 0:
+        check(rc, "pipesgd_bucket_plan")
+    return ([(int(out_b[i].start), int(out_b[i].n)) for i in range(rc)],
+            [int(out_o[i]) for i in range(nt)], int(n_packed.value))
+
+
+def segments_prepare(tensor_ptrs: Sequence[int], packed_ptrs: Sequence[int], numels: Sequence[int]):
+    """Returns (ctypes table ready to be copied to the device, total_tiles)."""
+    num = len(numels)
+    tab = (Segment * max(num, 1))()
+    for i in range(num):
+        tab[i].tensor, tab[i].packed, tab[i].numel, tab[i].first_tile = tensor_ptrs[i], packed_ptrs[i], numels[i], 0
+    total = C.c_uint64(0)
+    check(lib().pipesgd_segments_prepare(tab, num, C.byref(total)), "pipesgd_segments_prepare")
+    return tab, int(total.value)
+
+
+def pack(segments_dev, num: int, total_tiles: int, stream=None) -> None:
+    check(lib().pipesgd_pack(_ptr(segments_dev), num, total_tiles, _stream(stream)), "pipesgd_pack")
+
+
+def unpack(segments_dev, num: int, total_tiles: int, stream=None) -> None:
+    check(lib().pipesgd_unpack(_ptr(segments_dev), num, total_tiles, _stream(stream)), "pipesgd_unpack")

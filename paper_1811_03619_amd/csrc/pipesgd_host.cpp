@@ -1,0 +1,96 @@
+// Host-only parts of libpipesgd: size rules, the bucket planner, error text.
+// No device code and no HIP calls in this file.
+#include "pipesgd.h"
+
+namespace {
+constexpr uint64_t kTile = PIPESGD_QBLOCK;
+inline uint64_t round_up_tile(uint64_t x) { return (x + kTile - 1) / kTile * kTile; }
+}  // namespace
+
+extern "C" {
+
+const char *pipesgd_strerror(int err)
+{
+    switch (err) {
+    case PIPESGD_OK:           return "ok";
+    case PIPESGD_ERR_ARG:      return "invalid argument (null pointer, or a count/index out of range)";
+    case PIPESGD_ERR_ALIGN:    return "device pointer not 16-byte aligned, or bucket start not a multiple of 4096";
+    case PIPESGD_ERR_MODE:     return "unknown compression mode or schedule";
+    case PIPESGD_ERR_CAPACITY: return "too many workers or buckets, or output table too small";
+    case PIPESGD_ERR_HIP:      return "HIP runtime error at kernel launch";
+    default:                   return "unknown pipesgd error";
+    }
+}
+
+int pipesgd_version(void) { return PIPESGD_VERSION; }
+
+// n/p of Eq. 5, rounded to whole quantisation blocks.
+uint64_t pipesgd_chunk_elems(uint64_t n, int workers)
+{
+    if (workers < 1) return 0;
+    const uint64_t p = static_cast<uint64_t>(workers);
+    return round_up_tile((n + p - 1) / p);
+}
+
+uint64_t pipesgd_payload_bytes(int mode, uint64_t n)
+{
+    switch (mode) {
+    case PIPESGD_NONE:    return 4 * n;
+    case PIPESGD_TRUNC16: return 2 * n;     // the 2x of Sec. 4
+    case PIPESGD_QUANT8:  return n;         // the 4x of Sec. 4 (plus one scale per block)
+    default:              return 0;
+    }
+}
+
+uint64_t pipesgd_num_scales(int mode, uint64_t n)
+{
+    return mode == PIPESGD_QUANT8 ? (n + kTile - 1) / kTile : 0;
+}
+
+int pipesgd_bucket_plan(const uint64_t *numels, uint64_t num_tensors, uint64_t bucket_elems,
+                        pipesgd_bucket *buckets, uint64_t max_buckets,
+                        uint64_t *tensor_offsets, uint64_t *n_packed)
+{
+    if ((!numels && num_tensors) || !buckets || !tensor_offsets || !n_packed || bucket_elems == 0)
+        return PIPESGD_ERR_ARG;
+    uint64_t nb = 0, start = 0, fill = 0;
+    auto close_bucket = [&]() -> bool {
+        if (nb >= max_buckets) return false;
+        buckets[nb].start = start;
+        buckets[nb].n = fill;
+        ++nb;
+        start = round_up_tile(start + fill);
+        fill = 0;
+        return true;
+    };
+    for (uint64_t i = 0; i < num_tensors; ++i) {
+        if (fill > 0 && fill + numels[i] > bucket_elems) {
+            if (!close_bucket()) return PIPESGD_ERR_CAPACITY;
+        }
+        tensor_offsets[i] = start + fill;
+        fill += numels[i];
+    }
+    if (fill > 0 || nb == 0) {
+        if (!close_bucket()) return PIPESGD_ERR_CAPACITY;
+    }
+    *n_packed = round_up_tile(buckets[nb - 1].start + buckets[nb - 1].n);
+    if (nb > 0x7fffffffull) return PIPESGD_ERR_CAPACITY;
+    return static_cast<int>(nb);
+}
+
+int pipesgd_segments_prepare(pipesgd_segment *segments, uint64_t num, uint64_t *total_tiles)
+{
+    if ((!segments && num) || !total_tiles) return PIPESGD_ERR_ARG;
+    uint64_t tiles = 0;
+    for (uint64_t i = 0; i < num; ++i) {
+        if (segments[i].numel && (!segments[i].tensor || !segments[i].packed)) return PIPESGD_ERR_ARG;
+        if ((reinterpret_cast<uintptr_t>(segments[i].tensor) | reinterpret_cast<uintptr_t>(segments[i].packed)) & 3)
+            return PIPESGD_ERR_ALIGN;
+        segments[i].first_tile = tiles;
+        tiles += (segments[i].numel + kTile - 1) / kTile;
+    }
+    *total_tiles = tiles;
+    return PIPESGD_OK;
+}
+
+}  // extern "C"

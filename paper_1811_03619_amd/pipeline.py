@@ -1,0 +1,106 @@
+"""Buffer plumbing for a simulated Pipe-SGD job on one GPU: allocates the p
+workers' gradient, payload, model and momentum buffers with PyTorch and strings
+the library calls together in the order of Algorithm 1 (arXiv 1811.03619).
+No arithmetic happens in this file.
+
+Iteration t (width 2, the paper's optimal pipeline):
+    A[t]  = AllReduce(g_local[t])          -> slot[t % 2]
+    w[t]  = Update(w[t-1], slot[(t-1) % 2])   (slot starts as zero)
+The two calls touch disjoint buffers, which is what lets the paper overlap
+them; here they are enqueued back to back on one stream.
+"""
+from __future__ import annotations
+
+import ctypes as C
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+_PAYLOAD_TORCH = {B.NONE: torch.float32, B.TRUNC16: torch.int16, B.QUANT8: torch.int8}
+_PAYLOAD_NUMPY = {B.NONE: np.float32, B.TRUNC16: np.uint16, B.QUANT8: np.int8}
+
+
+def payload_empty(mode: int, n: int, device) -> torch.Tensor:
+    return torch.zeros(max(n, 1), dtype=_PAYLOAD_TORCH[mode], device=device)[:n]
+
+
+def payload_to_numpy(mode: int, t: torch.Tensor) -> np.ndarray:
+    a = t.detach().cpu().numpy()
+    return a.view(_PAYLOAD_NUMPY[mode]) if mode == B.TRUNC16 else a
+
+
+class PipeSgdSim:
+    """p simulated workers on one device."""
+
+    def __init__(self, mode: int, workers: int, n: int, lr: float, momentum: float = 0.0,
+                 grad_scale: float = 1.0, width: int = 2, buckets: Optional[Sequence[Tuple[int, int]]] = None,
+                 schedule: int = B.STEPWISE, device="cuda:0"):
+        assert width in (1, 2)
+        self.mode, self.p, self.n = mode, workers, n
+        self.lr, self.momentum, self.grad_scale, self.width = lr, momentum, grad_scale, width
+        self.schedule = schedule
+        self.device = torch.device(device)
+        self.buckets = list(buckets) if buckets else None
+        dev = self.device
+        ns = B.num_scales(mode, n)
+        self.g_local = [torch.zeros(max(n, 1), dtype=torch.float32, device=dev)[:n] for _ in range(workers)]
+        self.w = [torch.zeros(max(n, 1), dtype=torch.float32, device=dev)[:n] for _ in range(workers)]
+        self.v = [torch.zeros(max(n, 1), dtype=torch.float32, device=dev)[:n] for _ in range(workers)]
+        nslots = 2 if width == 2 else 1
+        self.slots = [[payload_empty(mode, n, dev) for _ in range(workers)] for _ in range(nslots)]
+        self.slot_scales = [[torch.zeros(max(ns, 1), dtype=torch.float32, device=dev)[:ns] for _ in range(workers)]
+                            for _ in range(nslots)]
+        self.rings = [B.make_ring(mode, n, self.g_local, self.slots[i],
+                                  self.slot_scales[i] if mode == B.QUANT8 else None, self.buckets)
+                      for i in range(nslots)]
+        self.updates = [B.UpdateArgs(self.slots[i], self.slot_scales[i] if mode == B.QUANT8 else None,
+                                     self.w, self.v if momentum != 0.0 else None)
+                        for i in range(nslots)]
+        self.t = 0
+
+    # -- data in / out (host <-> device copies; plumbing) --
+    def set_gradients(self, grads: Sequence[np.ndarray]) -> None:
+        for r, g in enumerate(grads):
+            self.g_local[r].copy_(torch.from_numpy(np.ascontiguousarray(g, dtype=np.float32)))
+
+    def set_model(self, w0: np.ndarray) -> None:
+        t = torch.from_numpy(np.ascontiguousarray(w0, dtype=np.float32))
+        for r in range(self.p):
+            self.w[r].copy_(t)
+
+    def model(self, r: int = 0) -> np.ndarray:
+        return self.w[r].detach().cpu().numpy()
+
+    def velocity(self, r: int = 0) -> np.ndarray:
+        return self.v[r].detach().cpu().numpy()
+
+    def result(self, r: int, which: Optional[int] = None):
+        """(payload, scales) of the most recent AllReduce on worker r."""
+        i = self._last if which is None else which
+        pay = payload_to_numpy(self.mode, self.slots[i][r])
+        sc = self.slot_scales[i][r].detach().cpu().numpy() if self.mode == B.QUANT8 else None
+        return pay, sc
+
+    # -- the path --
+    def allreduce(self, stream=None) -> int:
+        """Enqueue the AllReduce of the current gradients; returns the slot index."""
+        i = (self.t + 1) % len(self.rings)
+        B.allreduce_sim(self.rings[i], self.schedule, stream)
+        self._last = i
+        return i
+
+    def update_from(self, slot: int, stream=None) -> None:
+        B.apply_update_multi(self.mode, self.updates[slot], self.n, self.lr, self.momentum, self.grad_scale, stream)
+
+    def iteration(self, stream=None) -> None:
+        """One pass of the hot path: AllReduce of g_local[t] and the update that
+        yields w[t] (from the previous AllReduce's slot when width is 2)."""
+        cur = self.allreduce(stream)
+        if self.width == 2:
+            self.update_from(1 - cur, stream)
+        else:
+            self.update_from(cur, stream)
+        self.t += 1

@@ -1,0 +1,167 @@
+"""Host-side checks of libpipesgd that need no GPU: the library loads, exports
+every symbol the header declares, its size rules and bucket planner agree with
+the oracle's, and argument validation rejects bad calls before anything is
+launched.
+"""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_1811_03619_amd import binding as B
+from paper_1811_03619_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "pipesgd.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(pipesgd_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    L = B.lib()
+    names = declared_functions()
+    assert len(names) >= 17
+    for name in names:
+        assert hasattr(L, name), name
+    assert sorted(B.EXPORTS) == names
+    assert B.version() == 100
+    assert B.strerror(0) == "ok" and "aligned" in B.strerror(-2)
+
+
+def test_ring_struct_layout_matches_header():
+    # int32 x2, uint64, uint32 x2, pointer, 3 arrays of 16 pointers
+    assert C.sizeof(B.RingStruct) == 4 + 4 + 8 + 4 + 4 + 8 + 3 * 16 * 8
+    assert C.sizeof(B.Segment) == 32 and C.sizeof(B.Bucket) == 16
+    assert B.RingStruct.g_local.offset == 32
+
+
+@pytest.mark.parametrize("n", [0, 1, 4095, 4096, 4097, 648010, 1 << 20, 60965224, 138357544, 25557032])
+@pytest.mark.parametrize("p", [1, 2, 3, 4, 7, 16])
+def test_size_rules_agree_with_oracle(orc, n, p):
+    assert B.chunk_elems(n, p) == orc.chunk_elems(n, p)
+    for mode in (0, 1, 2):
+        assert B.num_scales(mode, n) == orc.num_scales(mode, n)
+        assert B.payload_bytes(mode, n) + 4 * B.num_scales(mode, n) == orc.payload_bytes(mode, n)
+    assert B.chunk_elems(n, 0) == 0 and B.payload_bytes(9, n) == 0
+
+
+@pytest.mark.parametrize("cap", [1, 4096, 16384, 1 << 20, 1 << 40])
+def test_bucket_plan_agrees_with_oracle(orc, cap):
+    cases = [
+        [10, 20, 5000, 3, 2_000_000, 7, 1 << 20, 1],
+        [t.numel for t in W.config_tensors(2)],
+        [t.numel for t in W.config_tensors(3)],
+        [1],
+        [4096, 4096, 4096],
+    ]
+    if cap >= 16384:
+        cases.append([t.numel for t in W.config_tensors(5)])
+    for numels in cases:
+        want = orc.bucket_plan(numels, cap)
+        if len(want[0]) > B.MAX_BUCKETS:
+            with pytest.raises(B.PipeSgdError):
+                B.bucket_plan(numels, cap)
+            got = B.bucket_plan(numels, cap, max_buckets=len(want[0]))
+        else:
+            got = B.bucket_plan(numels, cap)
+        assert got[0] == want[0] and got[1] == want[1] and got[2] == want[2]
+
+
+def test_bucket_plan_rejects_bad_arguments():
+    L = B.lib()
+    n_packed = C.c_uint64()
+    out_b = (B.Bucket * 4)()
+    out_o = (C.c_uint64 * 4)()
+    arr = (C.c_uint64 * 4)(1, 2, 3, 4)
+    assert L.pipesgd_bucket_plan(arr, 4, 0, out_b, 4, out_o, C.byref(n_packed)) == -1
+    assert L.pipesgd_bucket_plan(None, 4, 10, out_b, 4, out_o, C.byref(n_packed)) == -1
+    assert L.pipesgd_bucket_plan(arr, 4, 1, out_b, 2, out_o, C.byref(n_packed)) == -4
+    assert L.pipesgd_bucket_plan(arr, 0, 10, out_b, 4, out_o, C.byref(n_packed)) == 1     # one empty bucket
+    assert (out_b[0].start, out_b[0].n, n_packed.value) == (0, 0, 0)
+
+
+def test_segments_prepare():
+    tab, total = B.segments_prepare([4096, 8192, 16384], [65536, 65540, 131072], [1, 4096, 4097])
+    assert total == 1 + 1 + 2
+    assert [tab[i].first_tile for i in range(3)] == [0, 1, 2]
+    with pytest.raises(B.PipeSgdError):
+        B.segments_prepare([4097], [65536], [8])            # not 4-byte aligned
+    with pytest.raises(B.PipeSgdError):
+        B.segments_prepare([0], [65536], [8])               # null tensor
+
+
+# Validation happens before any HIP call, so these run without a GPU.  The
+# "device" addresses below are never dereferenced.
+
+def fake_ring(p=4, mode=B.NONE, n=8192, buckets=None, g=0x10000, pay=0x20000, sc=0x30000):
+    return B.make_ring(mode, n, [g] * p, [pay] * p, [sc] * p, buckets)
+
+
+def test_ring_validation_errors():
+    L = B.lib()
+    call = lambda R, step=0: L.pipesgd_ring_reduce_scatter_step(C.byref(R), step, None)
+    assert L.pipesgd_ring_reduce_scatter_step(None, 0, None) == -1
+    assert call(fake_ring(mode=7)) == -3
+    R = fake_ring(); R.workers = 0
+    assert call(R) == -1
+    R = fake_ring(); R.workers = 17
+    assert call(R) == -4
+    R = fake_ring(); R.reserved = 1
+    assert call(R) == -1
+    assert call(fake_ring(g=0x10004)) == -2
+    assert call(fake_ring(pay=0x20008)) == -2
+    assert call(fake_ring(g=0)) == -1
+    assert call(fake_ring(mode=B.QUANT8, sc=0)) == -1
+    assert call(fake_ring(), step=3) == -1                  # rounds are 0..p-2
+    assert call(fake_ring(), step=-1) == -1
+    assert call(fake_ring(p=1), step=0) == -1               # a single worker has no rounds
+    assert call(fake_ring(buckets=[(100, 50)])) == -2       # bucket start not a multiple of 4096
+    assert call(fake_ring(buckets=[(0, 5000), (4096, 100)])) == -1    # overlap
+    assert call(fake_ring(buckets=[(4096, 8192)])) == -1    # runs past n
+    R = fake_ring(buckets=[(0, 10)]); R.num_buckets = 65
+    assert call(R) == -4
+    assert L.pipesgd_allreduce_sim(C.byref(fake_ring()), 5, None) == -3
+    # an empty vector is valid and enqueues nothing
+    assert L.pipesgd_allreduce_sim(C.byref(fake_ring(n=0, g=0, pay=0, sc=0)), 0, None) == 0
+    assert L.pipesgd_ring_first_send(C.byref(fake_ring(n=0, g=0, pay=0, sc=0)), None) == 0
+
+
+def test_codec_and_update_validation_errors():
+    L = B.lib()
+    assert L.pipesgd_compress(5, 0x1000, 10, 0x2000, None, None) == -3
+    assert L.pipesgd_compress(0, None, 10, 0x2000, None, None) == -1
+    assert L.pipesgd_compress(2, 0x1000, 10, 0x2000, None, None) == -1        # QUANT8 needs scales
+    assert L.pipesgd_compress(1, 0x1004, 10, 0x2000, None, None) == -2
+    assert L.pipesgd_compress(1, None, 0, None, None, None) == 0               # n = 0: no-op
+    assert L.pipesgd_decompress(1, 0x2000, None, 10, None, None) == -1
+    assert L.pipesgd_decompress(2, 0x2000, 0x3004, 10, 0x1000, None) == -2
+    f = C.c_float
+    assert L.pipesgd_apply_update(0, 0x1000, None, 10, None, None, f(.1), f(0), f(1), None) == -1
+    assert L.pipesgd_apply_update(0, 0x1000, None, 10, 0x2000, None, f(.1), f(.9), f(1), None) == -1   # momentum needs v
+    assert L.pipesgd_apply_update(0, 0x1000, None, 10, 0x2008, None, f(.1), f(0), f(1), None) == -2
+    assert L.pipesgd_apply_update(3, 0x1000, None, 10, 0x2000, None, f(.1), f(0), f(1), None) == -3
+    assert L.pipesgd_apply_update(0, 0x1000, None, 0, 0x2000, None, f(.1), f(0), f(1), None) == 0
+    ptrs = (C.c_void_p * 17)(*([0x1000] * 17))
+    assert L.pipesgd_apply_update_multi(0, 17, ptrs, None, 10, ptrs, None, f(.1), f(0), f(1), None) == -4
+    assert L.pipesgd_apply_update_multi(0, 0, ptrs, None, 10, ptrs, None, f(.1), f(0), f(1), None) == -1
+    assert L.pipesgd_pack(None, 3, 3, None) == -1
+    assert L.pipesgd_pack(None, 0, 0, None) == 0
+
+
+def test_product_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_1811_03619_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for fn in files:
+            if fn.endswith((".py", ".hip", ".cpp", ".h")):
+                text = open(os.path.join(dirpath, fn)).read()
+                assert not re.search(r"^\s*(from|import)\s+oracle\b", text, flags=re.M), fn
+                assert "pipesgd_oracle" not in text, fn
+    for fn in os.listdir(os.path.join(ROOT, "oracle")):
+        if fn.endswith((".py", ".c")):
+            text = open(os.path.join(ROOT, "oracle", fn)).read()
+            assert "paper_1811_03619_amd" not in text and "pipesgd.h" not in text, fn
