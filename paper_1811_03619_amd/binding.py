@@ -63,9 +63,11 @@ def lib():
     global _lib
     if _lib is not None:
         return _lib
-    path = buildlib.LIB_PATH
-    if not os.path.exists(path):
-        buildlib.build(force=True)
+    path = os.environ.get("PIPESGD_LIB")            # a tuning variant built elsewhere
+    if not path:
+        path = buildlib.LIB_PATH
+        if not os.path.exists(path):
+            buildlib.build(force=True)
     try:
         L = C.CDLL(path)
     except OSError as e:                                    # pragma: no cover

@@ -38,20 +38,21 @@ def is_stale() -> bool:
     return any(os.path.getmtime(d) > t for d in deps)
 
 
-def build(force: bool = True, verbose: bool = False) -> str:
+def build(force: bool = True, verbose: bool = False, defines=(), out: str = LIB_PATH) -> str:
     """Compile the library.  force=False skips the work if the library is newer
-    than its sources."""
-    if not force and not is_stale():
+    than its sources.  `defines` ("NAME=VALUE") and `out` build a tuning variant
+    somewhere else."""
+    if not force and out == LIB_PATH and not is_stale():
         return LIB_PATH
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + ["-I", INCLUDE]
+    cmd = [hipcc] + HIPCC_FLAGS + ["-I", INCLUDE] + ["-D" + d for d in defines]
     for s in sources():
         cmd += ["-x", "hip", s]
-    cmd += ["-o", LIB_PATH]
+    cmd += ["-o", out]
     if verbose:
         print(" ".join(cmd))
     subprocess.check_call(cmd)
-    return LIB_PATH
+    return out
 
 
 if __name__ == "__main__":

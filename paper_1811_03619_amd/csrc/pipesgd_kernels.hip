@@ -35,6 +35,40 @@ static_assert(kThreads * kPerThread == kTile, "tile geometry");
 constexpr int kMaxW = PIPESGD_MAX_WORKERS;
 constexpr int kMaxB = PIPESGD_MAX_BUCKETS;
 
+// ------------------------------------------------- streaming memory access --
+// Native vector types (the nontemporal builtins take these, not HIP's structs).
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// Cache policy per stream.  "Streamed" data is touched once per launch and not
+// again soon: loading/storing it with the nontemporal hint keeps it from
+// displacing the hop payloads, which ARE re-read by the next launch.
+#ifndef PIPESGD_NT_GRAD
+#define PIPESGD_NT_GRAD 1        // local gradients: read once per iteration
+#endif
+#ifndef PIPESGD_NT_PAYIN
+#define PIPESGD_NT_PAYIN 1       // incoming hop payload: this is its last use
+#endif
+#ifndef PIPESGD_NT_PAYOUT
+#define PIPESGD_NT_PAYOUT 0      // outgoing hop payload: the next round reads it
+#endif
+#ifndef PIPESGD_NT_UPDATE
+#define PIPESGD_NT_UPDATE 1      // slot, w, v of the update: 2 GB streamed once
+#endif
+constexpr bool kNtGrad = PIPESGD_NT_GRAD, kNtPayIn = PIPESGD_NT_PAYIN, kNtPayOut = PIPESGD_NT_PAYOUT,
+               kNtUpdate = PIPESGD_NT_UPDATE;
+
+template <bool NT, typename V> __device__ __forceinline__ V ld(const V *p)
+{
+    if (NT) return __builtin_nontemporal_load(p);
+    return *p;
+}
+template <bool NT, typename V> __device__ __forceinline__ void st(V *p, V x)
+{
+    if (NT) __builtin_nontemporal_store(x, p); else *p = x;
+}
+
 // ------------------------------------------------------------ kernel args --
 
 // Bucket geometry, passed by value (lives in the kernarg segment, read with
@@ -144,16 +178,16 @@ __device__ __forceinline__ int sext8(uint32_t u, int byte)
 template <int MODE> struct Codec;
 
 template <> struct Codec<PIPESGD_NONE> {
-    using Raw = float4;
+    using Raw = f32x4;
     static constexpr int kBytes = 4;
     __device__ static void decode(const Raw &r, float, float *x) { x[0] = r.x; x[1] = r.y; x[2] = r.z; x[3] = r.w; }
-    __device__ static Raw encode(const float *x, float) { return make_float4(x[0], x[1], x[2], x[3]); }
+    __device__ static Raw encode(const float *x, float) { return Raw{x[0], x[1], x[2], x[3]}; }
     __device__ static float decode1(const void *pay, uint64_t i, float) { return static_cast<const float *>(pay)[i]; }
     __device__ static void encode1(void *pay, uint64_t i, float x, float) { static_cast<float *>(pay)[i] = x; }
 };
 
 template <> struct Codec<PIPESGD_TRUNC16> {
-    using Raw = uint2;                                      // four uint16, little endian
+    using Raw = u32x2;                                      // four uint16, little endian
     static constexpr int kBytes = 2;
     __device__ static void decode(const Raw &r, float, float *x)
     {
@@ -162,8 +196,8 @@ template <> struct Codec<PIPESGD_TRUNC16> {
     }
     __device__ static Raw encode(const float *x, float)
     {
-        return make_uint2((f2u(x[0]) >> 16) | (f2u(x[1]) & 0xffff0000u),
-                          (f2u(x[2]) >> 16) | (f2u(x[3]) & 0xffff0000u));
+        return Raw{(f2u(x[0]) >> 16) | (f2u(x[1]) & 0xffff0000u),
+                   (f2u(x[2]) >> 16) | (f2u(x[3]) & 0xffff0000u)};
     }
     __device__ static float decode1(const void *pay, uint64_t i, float)
     {
@@ -205,12 +239,13 @@ template <> struct Codec<PIPESGD_QUANT8> {
 // The *_full variants assume a whole, 16-byte aligned tile; the *_tail
 // variants guard every element against `len` and fill the rest with zero.
 
+template <bool NT>
 __device__ __forceinline__ void load_f32_full(const float *base, float *x)
 {
-    const float4 *v = reinterpret_cast<const float4 *>(base);
-    float4 r[kQuads];
+    const f32x4 *v = reinterpret_cast<const f32x4 *>(base);
+    f32x4 r[kQuads];
 #pragma unroll
-    for (int i = 0; i < kQuads; ++i) r[i] = v[i * kThreads + threadIdx.x];
+    for (int i = 0; i < kQuads; ++i) r[i] = ld<NT>(v + i * kThreads + threadIdx.x);
 #pragma unroll
     for (int i = 0; i < kQuads; ++i) { x[4 * i] = r[i].x; x[4 * i + 1] = r[i].y; x[4 * i + 2] = r[i].z; x[4 * i + 3] = r[i].w; }
 }
@@ -224,12 +259,13 @@ __device__ __forceinline__ void load_f32_tail(const float *base, uint32_t len, f
             x[4 * i + e] = idx < len ? base[idx] : 0.0f;
         }
 }
+template <bool NT>
 __device__ __forceinline__ void store_f32_full(float *base, const float *x)
 {
-    float4 *v = reinterpret_cast<float4 *>(base);
+    f32x4 *v = reinterpret_cast<f32x4 *>(base);
 #pragma unroll
     for (int i = 0; i < kQuads; ++i)
-        v[i * kThreads + threadIdx.x] = make_float4(x[4 * i], x[4 * i + 1], x[4 * i + 2], x[4 * i + 3]);
+        st<NT>(v + i * kThreads + threadIdx.x, f32x4{x[4 * i], x[4 * i + 1], x[4 * i + 2], x[4 * i + 3]});
 }
 __device__ __forceinline__ void store_f32_tail(float *base, uint32_t len, const float *x)
 {
@@ -244,7 +280,7 @@ __device__ __forceinline__ void store_f32_tail(float *base, uint32_t len, const 
 
 // Payload of a tile -> fp32.  `pay` points at the payload array's element 0,
 // e0 is the tile's first element, `scale` the tile's stored scale (QUANT8).
-template <int MODE, bool FULL>
+template <int MODE, bool FULL, bool NT>
 __device__ __forceinline__ void load_payload(const void *pay, uint64_t e0, uint32_t len, float scale, float *x)
 {
     using C = Codec<MODE>;
@@ -254,7 +290,7 @@ __device__ __forceinline__ void load_payload(const void *pay, uint64_t e0, uint3
             reinterpret_cast<const typename C::Raw *>(static_cast<const char *>(pay) + e0 * C::kBytes);
         typename C::Raw r[kQuads];
 #pragma unroll
-        for (int i = 0; i < kQuads; ++i) r[i] = v[i * kThreads + threadIdx.x];
+        for (int i = 0; i < kQuads; ++i) r[i] = ld<NT>(v + i * kThreads + threadIdx.x);
 #pragma unroll
         for (int i = 0; i < kQuads; ++i) C::decode(r[i], step, x + 4 * i);
     } else {
@@ -280,7 +316,7 @@ __device__ __forceinline__ float tile_absmax(const float *x, float *red)
 
 // fp32 -> payload of a tile.  For QUANT8 `scale` is the tile's range
 // (tile_absmax); it is stored by thread 0.
-template <int MODE, bool FULL>
+template <int MODE, bool FULL, bool NT>
 __device__ __forceinline__ void store_payload(void *pay, float *sc, uint64_t e0, uint32_t len, float scale, const float *x)
 {
     using C = Codec<MODE>;
@@ -288,7 +324,7 @@ __device__ __forceinline__ void store_payload(void *pay, float *sc, uint64_t e0,
     if (FULL) {
         typename C::Raw *v = reinterpret_cast<typename C::Raw *>(static_cast<char *>(pay) + e0 * C::kBytes);
 #pragma unroll
-        for (int i = 0; i < kQuads; ++i) v[i * kThreads + threadIdx.x] = C::encode(x + 4 * i, inv);
+        for (int i = 0; i < kQuads; ++i) st<NT>(v + i * kThreads + threadIdx.x, C::encode(x + 4 * i, inv));
     } else {
 #pragma unroll
         for (int i = 0; i < kQuads; ++i)
@@ -334,25 +370,25 @@ __global__ __launch_bounds__(kThreads) void ring_hop_kernel(RingArgs a, BucketTa
     const bool full = t.len == kTile;
 
     float P[kPerThread];
-    if (full) load_f32_full(a.g[r] + t.elem0, P); else load_f32_tail(a.g[r] + t.elem0, t.len, P);
+    if (full) load_f32_full<kNtGrad>(a.g[r] + t.elem0, P); else load_f32_tail(a.g[r] + t.elem0, t.len, P);
 
     if (HAS_IN) {
         const int src = mod_p(r - 1, a.p);
         float x[kPerThread];
         if (MODE == PIPESGD_NONE && in_is_grad) {
-            if (full) load_f32_full(a.g[src] + t.elem0, x); else load_f32_tail(a.g[src] + t.elem0, t.len, x);
+            if (full) load_f32_full<kNtGrad>(a.g[src] + t.elem0, x); else load_f32_tail(a.g[src] + t.elem0, t.len, x);
         } else {
             const float scale_in = MODE == PIPESGD_QUANT8 ? a.sc[src][t.elem0 / kTile] : 0.0f;
-            if (full) load_payload<MODE, true>(a.pay[src], t.elem0, t.len, scale_in, x);
-            else      load_payload<MODE, false>(a.pay[src], t.elem0, t.len, scale_in, x);
+            if (full) load_payload<MODE, true, kNtPayIn>(a.pay[src], t.elem0, t.len, scale_in, x);
+            else      load_payload<MODE, false, false>(a.pay[src], t.elem0, t.len, scale_in, x);
         }
 #pragma unroll
         for (int k = 0; k < kPerThread; ++k) P[k] = x[k] + P[k];
     }
 
     const float scale = MODE == PIPESGD_QUANT8 ? tile_absmax(P, red) : 0.0f;
-    if (full) store_payload<MODE, true>(a.pay[r], a.sc[r], t.elem0, t.len, scale, P);
-    else      store_payload<MODE, false>(a.pay[r], a.sc[r], t.elem0, t.len, scale, P);
+    if (full) store_payload<MODE, true, kNtPayOut>(a.pay[r], a.sc[r], t.elem0, t.len, scale, P);
+    else      store_payload<MODE, false, false>(a.pay[r], a.sc[r], t.elem0, t.len, scale, P);
 }
 
 // One send-back round for every worker: byte copy of a chunk's payload (and
@@ -370,14 +406,14 @@ __global__ __launch_bounds__(kThreads) void ring_allgather_kernel(RingArgs a, Bu
     char *out = static_cast<char *>(a.pay[r]) + t.elem0 * C::kBytes;
     if (t.len == kTile) {
         constexpr int kVecs = kTile * C::kBytes / 16;          // 1024, 512 or 256 16-byte vectors
-        const uint4 *vi = reinterpret_cast<const uint4 *>(in);
-        uint4 *vo = reinterpret_cast<uint4 *>(out);
+        const u32x4 *vi = reinterpret_cast<const u32x4 *>(in);
+        u32x4 *vo = reinterpret_cast<u32x4 *>(out);
         constexpr int kIter = kVecs / kThreads;
-        uint4 tmp[kIter];
+        u32x4 tmp[kIter];
 #pragma unroll
-        for (int i = 0; i < kIter; ++i) tmp[i] = vi[i * kThreads + threadIdx.x];
+        for (int i = 0; i < kIter; ++i) tmp[i] = ld<kNtPayIn>(vi + i * kThreads + threadIdx.x);
 #pragma unroll
-        for (int i = 0; i < kIter; ++i) vo[i * kThreads + threadIdx.x] = tmp[i];
+        for (int i = 0; i < kIter; ++i) st<kNtPayOut>(vo + i * kThreads + threadIdx.x, tmp[i]);
     } else {
         const uint32_t bytes = t.len * C::kBytes;
         for (uint32_t i = threadIdx.x; i < bytes; i += kThreads) out[i] = in[i];
@@ -398,11 +434,11 @@ __global__ __launch_bounds__(kThreads) void ring_fused_kernel(RingArgs a, Bucket
     const int p = a.p;
 
     float P[kPerThread], g[kPerThread];
-    if (full) load_f32_full(a.g[c] + t.elem0, P); else load_f32_tail(a.g[c] + t.elem0, t.len, P);
+    if (full) load_f32_full<kNtGrad>(a.g[c] + t.elem0, P); else load_f32_tail(a.g[c] + t.elem0, t.len, P);
     int flip = 0;
     for (int j = 1; j < p; ++j) {
         const int wkr = mod_p(c + j, p);
-        if (full) load_f32_full(a.g[wkr] + t.elem0, g); else load_f32_tail(a.g[wkr] + t.elem0, t.len, g);
+        if (full) load_f32_full<kNtGrad>(a.g[wkr] + t.elem0, g); else load_f32_tail(a.g[wkr] + t.elem0, t.len, g);
         float scale = 0.0f;
         if (MODE == PIPESGD_QUANT8) { scale = tile_absmax(P, red[flip]); flip ^= 1; }
         through_the_wire<MODE>(P, scale);
@@ -412,8 +448,8 @@ __global__ __launch_bounds__(kThreads) void ring_fused_kernel(RingArgs a, Bucket
     float scale = 0.0f;
     if (MODE == PIPESGD_QUANT8) scale = tile_absmax(P, red[flip]);
     for (int r = 0; r < p; ++r) {
-        if (full) store_payload<MODE, true>(a.pay[r], a.sc[r], t.elem0, t.len, scale, P);
-        else      store_payload<MODE, false>(a.pay[r], a.sc[r], t.elem0, t.len, scale, P);
+        if (full) store_payload<MODE, true, true>(a.pay[r], a.sc[r], t.elem0, t.len, scale, P);
+        else      store_payload<MODE, false, false>(a.pay[r], a.sc[r], t.elem0, t.len, scale, P);
     }
 }
 
@@ -426,10 +462,10 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(const float *src, ui
     const uint64_t rem = n - e0;
     const uint32_t len = rem < static_cast<uint64_t>(kTile) ? static_cast<uint32_t>(rem) : kTile;
     float x[kPerThread];
-    if (len == kTile) load_f32_full(src + e0, x); else load_f32_tail(src + e0, len, x);
+    if (len == kTile) load_f32_full<true>(src + e0, x); else load_f32_tail(src + e0, len, x);
     const float scale = MODE == PIPESGD_QUANT8 ? tile_absmax(x, red) : 0.0f;
-    if (len == kTile) store_payload<MODE, true>(pay, sc, e0, len, scale, x);
-    else              store_payload<MODE, false>(pay, sc, e0, len, scale, x);
+    if (len == kTile) store_payload<MODE, true, false>(pay, sc, e0, len, scale, x);
+    else              store_payload<MODE, false, false>(pay, sc, e0, len, scale, x);
 }
 
 template <int MODE>
@@ -440,8 +476,8 @@ __global__ __launch_bounds__(kThreads) void decompress_kernel(const void *pay, c
     const uint32_t len = rem < static_cast<uint64_t>(kTile) ? static_cast<uint32_t>(rem) : kTile;
     const float scale = MODE == PIPESGD_QUANT8 ? sc[blockIdx.x] : 0.0f;
     float x[kPerThread];
-    if (len == kTile) { load_payload<MODE, true>(pay, e0, len, scale, x); store_f32_full(dst + e0, x); }
-    else              { load_payload<MODE, false>(pay, e0, len, scale, x); store_f32_tail(dst + e0, len, x); }
+    if (len == kTile) { load_payload<MODE, true, true>(pay, e0, len, scale, x); store_f32_full<false>(dst + e0, x); }
+    else              { load_payload<MODE, false, false>(pay, e0, len, scale, x); store_f32_tail(dst + e0, len, x); }
 }
 
 // Decompress + momentum-SGD step (Alg. 1 compute thread lines 4-5) for every
@@ -460,11 +496,11 @@ __global__ __launch_bounds__(kThreads) void update_kernel(UpdateArgs a)
 
     float g[kPerThread], wv[kPerThread], vv[kPerThread];
     if (full) {
-        load_payload<MODE, true>(a.pay[r], e0, len, scale, g);
-        load_f32_full(w, wv);
-        if (MOMENTUM) load_f32_full(v, vv);
+        load_payload<MODE, true, kNtUpdate>(a.pay[r], e0, len, scale, g);
+        load_f32_full<kNtUpdate>(w, wv);
+        if (MOMENTUM) load_f32_full<kNtUpdate>(v, vv);
     } else {
-        load_payload<MODE, false>(a.pay[r], e0, len, scale, g);
+        load_payload<MODE, false, false>(a.pay[r], e0, len, scale, g);
         load_f32_tail(w, len, wv);
         if (MOMENTUM) load_f32_tail(v, len, vv);
     }
@@ -483,8 +519,8 @@ __global__ __launch_bounds__(kThreads) void update_kernel(UpdateArgs a)
         }
     }
     if (full) {
-        if (MOMENTUM) store_f32_full(v, vv);
-        store_f32_full(w, wv);
+        if (MOMENTUM) store_f32_full<kNtUpdate>(v, vv);
+        store_f32_full<kNtUpdate>(w, wv);
     } else {
         if (MOMENTUM) store_f32_tail(v, len, vv);
         store_f32_tail(w, len, wv);
@@ -513,8 +549,8 @@ __global__ __launch_bounds__(kThreads) void segment_copy_kernel(const pipesgd_se
         ((reinterpret_cast<uintptr_t>(in) | reinterpret_cast<uintptr_t>(out)) & 15) == 0;
     if (vec) {
         float x[kPerThread];
-        load_f32_full(in, x);
-        store_f32_full(out, x);
+        load_f32_full<true>(in, x);
+        store_f32_full<false>(out, x);
     } else {
         for (uint32_t i = threadIdx.x; i < len; i += kThreads) out[i] = in[i];
     }
