@@ -57,6 +57,10 @@ def main() -> int:
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle timing (0 = skip)")
     ap.add_argument("--phases", action="store_true", help="also time each phase separately")
+    ap.add_argument("--calib-copy", type=int, default=0,
+                    help="after the timed region, launch this many plain copies of one worker's gradient "
+                         "(pipesgd_compress in mode NONE: reads 4n, writes 4n bytes) so that a rocprofv3 --pmc "
+                         "run of this command holds a kernel of known traffic to scale its counters by")
     args = ap.parse_args()
 
     if args.gpus != 1:
@@ -132,16 +136,7 @@ def main() -> int:
     value = model["total"] / (ms_per_step * 1e-3) / 1e9
     upd_gbs = model["update"] / (upd_ms * 1e-3) / 1e9
 
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "update_traffic.json")
-    if os.path.exists(tpath):
-        try:
-            rec = json.load(open(tpath))
-            key = f"config{cfg}_mode{mode}"
-            if key in rec:
-                traffic = rec[key]
-        except Exception:
-            traffic = None
+    traffic = committed_traffic(cfg, ["none", "trunc16", "quant8"][mode])
 
     out = {
         "metric": "aggregation+update GB/s (fraction of HBM peak) and iters/s at K=4, 61M params",
@@ -178,11 +173,32 @@ def main() -> int:
     if args.phases:
         out["phases_ms"] = time_phases(sim, B, torch, np)
 
+    if args.calib_copy > 0:
+        dst = torch.empty_like(sim.g_local[0])
+        for _ in range(args.calib_copy):
+            B.compress(B.NONE, sim.g_local[0], n, dst, None)
+        torch.cuda.synchronize()
+        out["calib_copy"] = {"kernel": "compress_kernel<0>", "launches": args.calib_copy,
+                             "read_bytes_per_launch": 4 * n, "write_bytes_per_launch": 4 * n}
+
     if args.cpu_seconds > 0:
         out["cpu_baseline"] = cpu_baseline(mode, grads, w0, p, args.lr, momentum, buckets, model["total"],
                                            args.cpu_seconds)
     print(json.dumps(out), flush=True)
     return 0
+
+
+def committed_traffic(cfg: int, mode_name: str):
+    """HBM-side bytes per update launch from the committed rocprofv3 --pmc
+    summary of this workload (FETCH_SIZE and WRITE_SIZE runs, scaled by a copy
+    kernel of known size); None if no summary exists for it."""
+    import glob
+    import re
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", f"pmc_traffic_config{cfg}_*{mode_name}*.txt"))):
+        m = re.search(r"^update_kernel traffic_bytes_per_launch = (\d+)", open(path).read(), flags=re.M)
+        if m:
+            return int(m.group(1))
+    return None
 
 
 def time_phases(sim, B, torch, np, reps: int = 20):
