@@ -32,13 +32,19 @@ def payload_bytes_per_elem(mode: int) -> float:
     return {0: 4.0, 1: 2.0, 2: 1.0 + 4.0 / 4096.0}[mode]
 
 
-def bytes_model(mode: int, n: int, p: int, momentum: bool):
-    """Algorithmic bytes of one iteration, by phase (stepwise schedule)."""
+def bytes_model(mode: int, n: int, p: int, momentum: bool, fused: bool = False):
+    """Algorithmic bytes of one iteration, by phase.  Stepwise schedule: every
+    hop's payload is written once and read once.  Fused schedule: each gradient
+    is read once and each worker's result written once (hop payloads never
+    reach memory), so it is priced with its own, smaller byte count."""
     cb = payload_bytes_per_elem(mode)
+    upd = p * n * (cb + (16.0 if momentum else 8.0))
+    if fused:
+        ar = (4.0 * p + cb * p) * n
+        return {"allreduce_fused": ar, "update": upd, "total": ar + upd}
     first = 0.0 if mode == 0 else (4.0 + cb) * n
     rs = (p - 1) * n * (cb + 4.0 + cb)
     ag = (p - 1) * n * 2.0 * cb
-    upd = p * n * (cb + (16.0 if momentum else 8.0))
     return {"first_send": first, "reduce_scatter": rs, "allgather": ag, "update": upd,
             "total": first + rs + ag + upd}
 
@@ -132,7 +138,7 @@ def main() -> int:
     gpu_ms_per_step = start_ev.elapsed_time(stop_ev) / args.steps
     upd_ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
 
-    model = bytes_model(mode, n, p, momentum != 0.0)
+    model = bytes_model(mode, n, p, momentum != 0.0, fused=(schedule == B.FUSED))
     value = model["total"] / (ms_per_step * 1e-3) / 1e9
     upd_gbs = model["update"] / (upd_ms * 1e-3) / 1e9
 

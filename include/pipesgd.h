@@ -213,6 +213,32 @@ int pipesgd_segments_prepare(pipesgd_segment *segments, uint64_t num, uint64_t *
 int pipesgd_pack(const pipesgd_segment *segments, uint64_t num, uint64_t total_tiles, void *stream);
 int pipesgd_unpack(const pipesgd_segment *segments, uint64_t num, uint64_t total_tiles, void *stream);
 
+/* ----------------------------------------------------------------- tuning -- */
+
+/* Launch geometry of one kernel family for one compression mode.  Optional:
+ * the built-in defaults are the measured best on MI355X for 60M-element
+ * gradients.  A workgroup has `threads` threads, each handling `quads` groups of
+ * 4 consecutive elements (for the all-gather copy: `quads` 16-byte vectors);
+ * `lds_bytes` of LDS are reserved per workgroup for no other purpose than to cap
+ * how many workgroups a compute unit holds at once (0 = no cap): HBM delivers
+ * its best rate with fewer requests in flight than full occupancy issues.
+ * Supported (threads, quads): (64,4) (128,2) (128,4) (256,1) (256,2) (256,4)
+ * (512,1) (512,2) (1024,1); QUANT8 kernels that compute a block's range need
+ * threads*quads == 1024; the all-gather copy needs threads*quads*16 bytes to
+ * divide a tile's payload.  0 <= lds_bytes <= 162816 (159 KiB).
+ * The table is process-global and not synchronised: set it before launching
+ * from several threads.  Returns PIPESGD_ERR_ARG for an unsupported combination
+ * (the table is left unchanged).  Results never depend on it. */
+#define PIPESGD_K_FIRST_SEND      0
+#define PIPESGD_K_REDUCE_SCATTER  1
+#define PIPESGD_K_ALLGATHER       2
+#define PIPESGD_K_FUSED           3
+#define PIPESGD_K_UPDATE          4
+#define PIPESGD_K_COMPRESS        5
+#define PIPESGD_K_DECOMPRESS      6
+int pipesgd_set_launch_config(int kernel, int mode, int threads, int quads, int lds_bytes);
+int pipesgd_get_launch_config(int kernel, int mode, int *threads, int *quads, int *lds_bytes);
+
 #ifdef __cplusplus
 }
 #endif

@@ -25,7 +25,9 @@ EXPORTS = [
     "pipesgd_ring_reduce_scatter_step", "pipesgd_ring_allgather_step", "pipesgd_allreduce_sim",
     "pipesgd_apply_update", "pipesgd_apply_update_multi", "pipesgd_bucket_plan",
     "pipesgd_segments_prepare", "pipesgd_pack", "pipesgd_unpack",
+    "pipesgd_set_launch_config", "pipesgd_get_launch_config",
 ]
+K_FIRST_SEND, K_REDUCE_SCATTER, K_ALLGATHER, K_FUSED, K_UPDATE, K_COMPRESS, K_DECOMPRESS = range(7)
 
 
 class PipeSgdError(RuntimeError):
@@ -108,6 +110,10 @@ def lib():
     L.pipesgd_pack.argtypes = [vp, u64, u64, vp]
     L.pipesgd_unpack.restype = i32
     L.pipesgd_unpack.argtypes = [vp, u64, u64, vp]
+    L.pipesgd_set_launch_config.restype = i32
+    L.pipesgd_set_launch_config.argtypes = [i32, i32, i32, i32, i32]
+    L.pipesgd_get_launch_config.restype = i32
+    L.pipesgd_get_launch_config.argtypes = [i32, i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(i32)]
     _lib = L
     return L
 
@@ -238,6 +244,17 @@ def apply_update_multi(mode: int, args: UpdateArgs, n: int, lr: float, momentum:
     check(lib().pipesgd_apply_update_multi(mode, args.replicas, args.g_sum_c, args.scales, n, args.w, args.v,
                                            lr, momentum, grad_scale, _stream(stream)),
           "pipesgd_apply_update_multi")
+
+
+def set_launch_config(kernel: int, mode: int, threads: int, quads: int, lds_bytes: int = 0) -> None:
+    check(lib().pipesgd_set_launch_config(kernel, mode, threads, quads, lds_bytes), "pipesgd_set_launch_config")
+
+
+def get_launch_config(kernel: int, mode: int) -> Tuple[int, int, int]:
+    t, q, l = C.c_int(), C.c_int(), C.c_int()
+    check(lib().pipesgd_get_launch_config(kernel, mode, C.byref(t), C.byref(q), C.byref(l)),
+          "pipesgd_get_launch_config")
+    return t.value, q.value, l.value
 
 
 def bucket_plan(numels: Sequence[int], bucket_elems: int = 1 << 20, max_buckets: int = MAX_BUCKETS):

@@ -3,21 +3,28 @@
 // Everything here streams: each element is read, combined with one or two
 // other streams and written, a handful of ALU operations per 6..20 bytes.  The
 // bound is HBM bandwidth, so the kernels are organised around memory access:
-//   * the unit of work is one TILE of 4096 consecutive elements (= one
-//     quantisation block, = 16 KiB of fp32), handled by one 256-thread group;
-//   * a thread owns 4 "quads" (4 consecutive elements each) spaced 256 quads
-//     apart, so that every wave-level access is one contiguous run: 16 B per
-//     lane on fp32 streams, 8 B per lane on 16-bit payloads, 4 B per lane on
-//     8-bit payloads; all of a thread's loads are issued before any use;
-//   * ring blocks, bucket starts and therefore tiles are 4096-aligned, which
-//     makes every full tile vector-aligned; only the last tile of a ring block
-//     can be short and takes a guarded scalar path;
+//   * data is addressed in TILES of 4096 consecutive elements (= one
+//     quantisation block = 16 KiB of fp32).  Ring blocks and bucket starts are
+//     4096-aligned, so every whole tile is vector-aligned; only the last tile of
+//     a ring block can be short and takes a guarded scalar path;
+//   * a workgroup of THREADS threads handles one UNIT = THREADS*QUADS quads of
+//     a tile (a quad = 4 consecutive elements); a thread owns QUADS quads spaced
+//     THREADS quads apart, so every wave-level access is one contiguous run
+//     (16 B per lane on fp32, 8 B on 16-bit payloads, 4 B on 8-bit payloads),
+//     and all of a thread's loads are issued before the first use;
+//   * the (THREADS, QUADS) geometry and an LDS reservation that caps the number
+//     of resident workgroups per compute unit are launch parameters: measured
+//     on MI355X, HBM delivers its best rate with roughly 20-30 KB of loads in
+//     flight per compute unit -- far fewer than full occupancy would issue;
+//   * streamed operands use nontemporal loads/stores, hop payloads that the
+//     next launch re-reads use normal stores;
 //   * no matrix cores: nothing on this path is a contraction.
 // Arithmetic is written so that each operation is exactly one IEEE binary32
 // rounding (contraction is switched off for the file; the update's two fused
 // multiply-adds are explicit).
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cfloat>
 #include <cstdint>
 
@@ -28,12 +35,20 @@
 namespace {
 
 constexpr int kTile = PIPESGD_QBLOCK;        // elements per tile
-constexpr int kThreads = 256;                // 4 wavefronts of 64
-constexpr int kQuads = 4;                    // quads per thread per tile
-constexpr int kPerThread = 4 * kQuads;       // 16 elements
-static_assert(kThreads * kPerThread == kTile, "tile geometry");
+constexpr int kTileQuads = kTile / 4;
 constexpr int kMaxW = PIPESGD_MAX_WORKERS;
 constexpr int kMaxB = PIPESGD_MAX_BUCKETS;
+
+// Workgroup geometry.  kUnit elements per workgroup; kSplit units per tile.
+template <int THREADS, int QUADS> struct Geo {
+    static constexpr int kThreads = THREADS;
+    static constexpr int kQuads = QUADS;
+    static constexpr int kPerThread = 4 * QUADS;
+    static constexpr int kUnit = THREADS * QUADS * 4;
+    static constexpr int kSplit = kTile / kUnit;
+    static constexpr int kWaves = THREADS / 64;
+    static_assert(THREADS % 64 == 0 && kUnit <= kTile && kTile % kUnit == 0, "geometry");
+};
 
 // ------------------------------------------------- streaming memory access --
 // Native vector types (the nontemporal builtins take these, not HIP's structs).
@@ -99,9 +114,14 @@ struct UpdateArgs {
     float lr, momentum, grad_scale;
 };
 
-struct TileRef {
+// The full/short decision and the short length are deliberately kept as two
+// separate values (a flag and a plain truncation) instead of one clamped length:
+// the kernels branch on `full` once and the short body reads `len` as is.
+struct UnitRef {
     uint64_t elem0;     // first element, packed-buffer coordinates
-    uint32_t len;       // 1..4096, or 0 if the slot is empty for this chunk
+    uint32_t len;       // elements to process; meaningful only when !full (then 1..kUnit-1)
+    bool full;          // a whole unit of kUnit elements
+    bool empty;         // nothing to do
 };
 
 __device__ __forceinline__ int mod_p(int a, int p)
@@ -110,9 +130,13 @@ __device__ __forceinline__ int mod_p(int a, int p)
     return m < 0 ? m + p : m;
 }
 
-// Slot -> (bucket, tile of chunk `chunk`).  All operands are wave-uniform.
-__device__ __forceinline__ TileRef locate(const BucketTable &bt, uint32_t slot, int chunk)
+// blockIdx.x -> (bucket, tile of chunk `chunk`, unit of that tile).  All
+// operands are wave-uniform.
+template <class G>
+__device__ __forceinline__ UnitRef locate(const BucketTable &bt, uint32_t block, int chunk)
 {
+    const uint32_t slot = block / G::kSplit;
+    const uint32_t sub = block % G::kSplit;
     uint32_t lo = 0, hi = bt.count;
     while (hi - lo > 1) {
         const uint32_t mid = (lo + hi) >> 1;
@@ -121,14 +145,35 @@ __device__ __forceinline__ TileRef locate(const BucketTable &bt, uint32_t slot, 
     const uint64_t ce = static_cast<uint64_t>(bt.ce_tiles[lo]) * kTile;
     const uint64_t t = slot - bt.slot_prefix[lo];
     const uint64_t nb = bt.n[lo];
-    const uint64_t lo_e = static_cast<uint64_t>(chunk) * ce + t * kTile;
+    const uint64_t lo_e = static_cast<uint64_t>(chunk) * ce + t * kTile + static_cast<uint64_t>(sub) * G::kUnit;
     uint64_t hi_e = (static_cast<uint64_t>(chunk) + 1) * ce;
     if (hi_e > nb) hi_e = nb;
-    TileRef r;
-    if (lo_e >= hi_e) { r.elem0 = 0; r.len = 0; return r; }
+    UnitRef r;
+    r.empty = lo_e >= hi_e;
     r.elem0 = bt.start[lo] + lo_e;
     const uint64_t rem = hi_e - lo_e;
-    r.len = rem < static_cast<uint64_t>(kTile) ? static_cast<uint32_t>(rem) : static_cast<uint32_t>(kTile);
+    r.full = rem >= static_cast<uint64_t>(G::kUnit);
+    r.len = static_cast<uint32_t>(rem);
+    return r;
+}
+
+// Addressing-only geometry: UNIT elements per workgroup.
+template <int UNIT> struct UnitOnly {
+    static constexpr int kUnit = UNIT;
+    static constexpr int kSplit = kTile / UNIT;
+    static_assert(UNIT <= kTile && kTile % UNIT == 0, "unit");
+};
+
+// Unit of a flat vector.
+template <class G>
+__device__ __forceinline__ UnitRef locate_flat(uint64_t n, uint32_t block)
+{
+    UnitRef r;
+    r.elem0 = static_cast<uint64_t>(block) * G::kUnit;
+    const uint64_t rem = n - r.elem0;           // the grid has ceil(n / kUnit) blocks: rem >= 1
+    r.empty = false;
+    r.full = rem >= static_cast<uint64_t>(G::kUnit);
+    r.len = static_cast<uint32_t>(rem);
     return r;
 }
 
@@ -141,14 +186,19 @@ __device__ __forceinline__ float wave_max(float v)
     return v;
 }
 
-// red: 4 floats of LDS, one per wavefront.  One barrier per call; callers that
+// red: one float of LDS per wavefront.  One barrier per call; callers that
 // reduce repeatedly alternate between two such arrays.
+template <class G>
 __device__ __forceinline__ float block_max(float v, float *red)
 {
     v = wave_max(v);
+    if (G::kWaves == 1) return v;
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
     __syncthreads();
-    return fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    float m = red[0];
+#pragma unroll
+    for (int i = 1; i < G::kWaves; ++i) m = fmaxf(m, red[i]);
+    return m;
 }
 
 // ----------------------------------------------------------------- codecs --
@@ -234,53 +284,62 @@ template <> struct Codec<PIPESGD_QUANT8> {
     }
 };
 
-// ------------------------------------------------------- tile load / store --
-// x[16] of a thread: x[4*i + e] = element 4*(i*256 + tid) + e of the tile.
-// The *_full variants assume a whole, 16-byte aligned tile; the *_tail
+// ------------------------------------------------------- unit load / store --
+// x[4*QUADS] of a thread: x[4*i + e] = element 4*(i*THREADS + tid) + e of the
+// unit.  The *_full variants assume a whole, 16-byte aligned unit; the *_tail
 // variants guard every element against `len` and fill the rest with zero.
+// FULL is a template parameter everywhere: a kernel decides once per workgroup
+// which body to run, so that in the full body nothing separates the loads and
+// they are all in flight together.
 
-template <bool NT>
+template <class G, bool NT>
 __device__ __forceinline__ void load_f32_full(const float *base, float *x)
 {
     const f32x4 *v = reinterpret_cast<const f32x4 *>(base);
-    f32x4 r[kQuads];
+    f32x4 r[G::kQuads];
 #pragma unroll
-    for (int i = 0; i < kQuads; ++i) r[i] = ld<NT>(v + i * kThreads + threadIdx.x);
+    for (int i = 0; i < G::kQuads; ++i) r[i] = ld<NT>(v + i * G::kThreads + threadIdx.x);
 #pragma unroll
-    for (int i = 0; i < kQuads; ++i) { x[4 * i] = r[i].x; x[4 * i + 1] = r[i].y; x[4 * i + 2] = r[i].z; x[4 * i + 3] = r[i].w; }
+    for (int i = 0; i < G::kQuads; ++i) { x[4 * i] = r[i].x; x[4 * i + 1] = r[i].y; x[4 * i + 2] = r[i].z; x[4 * i + 3] = r[i].w; }
 }
+template <class G>
 __device__ __forceinline__ void load_f32_tail(const float *base, uint32_t len, float *x)
 {
 #pragma unroll
-    for (int i = 0; i < kQuads; ++i)
+    for (int i = 0; i < G::kQuads; ++i)
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const uint32_t idx = 4 * (i * kThreads + threadIdx.x) + e;
+            const uint32_t idx = 4 * (i * G::kThreads + threadIdx.x) + e;
             x[4 * i + e] = idx < len ? base[idx] : 0.0f;
         }
 }
-template <bool NT>
-__device__ __forceinline__ void store_f32_full(float *base, const float *x)
+template <class G, bool FULL, bool NT>
+__device__ __forceinline__ void load_f32(const float *base, uint32_t len, float *x)
 {
-    f32x4 *v = reinterpret_cast<f32x4 *>(base);
-#pragma unroll
-    for (int i = 0; i < kQuads; ++i)
-        st<NT>(v + i * kThreads + threadIdx.x, f32x4{x[4 * i], x[4 * i + 1], x[4 * i + 2], x[4 * i + 3]});
+    if (FULL) load_f32_full<G, NT>(base, x); else load_f32_tail<G>(base, len, x);
 }
-__device__ __forceinline__ void store_f32_tail(float *base, uint32_t len, const float *x)
+template <class G, bool FULL, bool NT>
+__device__ __forceinline__ void store_f32(float *base, uint32_t len, const float *x)
 {
+    if (FULL) {
+        f32x4 *v = reinterpret_cast<f32x4 *>(base);
 #pragma unroll
-    for (int i = 0; i < kQuads; ++i)
+        for (int i = 0; i < G::kQuads; ++i)
+            st<NT>(v + i * G::kThreads + threadIdx.x, f32x4{x[4 * i], x[4 * i + 1], x[4 * i + 2], x[4 * i + 3]});
+    } else {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const uint32_t idx = 4 * (i * kThreads + threadIdx.x) + e;
-            if (idx < len) base[idx] = x[4 * i + e];
-        }
+        for (int i = 0; i < G::kQuads; ++i)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t idx = 4 * (i * G::kThreads + threadIdx.x) + e;
+                if (idx < len) base[idx] = x[4 * i + e];
+            }
+    }
 }
 
-// Payload of a tile -> fp32.  `pay` points at the payload array's element 0,
-// e0 is the tile's first element, `scale` the tile's stored scale (QUANT8).
-template <int MODE, bool FULL, bool NT>
+// Payload of a unit -> fp32.  `pay` points at the payload array's element 0,
+// e0 is the unit's first element, `scale` the stored scale of its tile (QUANT8).
+template <int MODE, class G, bool FULL, bool NT>
 __device__ __forceinline__ void load_payload(const void *pay, uint64_t e0, uint32_t len, float scale, float *x)
 {
     using C = Codec<MODE>;
@@ -288,35 +347,38 @@ __device__ __forceinline__ void load_payload(const void *pay, uint64_t e0, uint3
     if (FULL) {
         const typename C::Raw *v =
             reinterpret_cast<const typename C::Raw *>(static_cast<const char *>(pay) + e0 * C::kBytes);
-        typename C::Raw r[kQuads];
+        typename C::Raw r[G::kQuads];
 #pragma unroll
-        for (int i = 0; i < kQuads; ++i) r[i] = ld<NT>(v + i * kThreads + threadIdx.x);
+        for (int i = 0; i < G::kQuads; ++i) r[i] = ld<NT>(v + i * G::kThreads + threadIdx.x);
 #pragma unroll
-        for (int i = 0; i < kQuads; ++i) C::decode(r[i], step, x + 4 * i);
+        for (int i = 0; i < G::kQuads; ++i) C::decode(r[i], step, x + 4 * i);
     } else {
 #pragma unroll
-        for (int i = 0; i < kQuads; ++i)
+        for (int i = 0; i < G::kQuads; ++i)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const uint32_t idx = 4 * (i * kThreads + threadIdx.x) + e;
+                const uint32_t idx = 4 * (i * G::kThreads + threadIdx.x) + e;
                 x[4 * i + e] = idx < len ? C::decode1(pay, e0 + idx, step) : 0.0f;
             }
     }
 }
 
-// Largest magnitude of the tile (QUANT8's range, Sec. 3.2).  Elements past
-// `len` were loaded as zero and do not disturb it.
+// Largest magnitude of a whole tile (QUANT8's range, Sec. 3.2); needs a
+// geometry whose unit is the tile.  Elements past `len` were loaded as zero
+// and do not disturb it.
+template <class G>
 __device__ __forceinline__ float tile_absmax(const float *x, float *red)
 {
+    static_assert(G::kUnit == kTile, "the quantisation range needs the whole block in one workgroup");
     float m = 0.0f;
 #pragma unroll
-    for (int k = 0; k < kPerThread; ++k) m = fmaxf(m, fabsf(x[k]));
-    return block_max(m, red);
+    for (int k = 0; k < G::kPerThread; ++k) m = fmaxf(m, fabsf(x[k]));
+    return block_max<G>(m, red);
 }
 
-// fp32 -> payload of a tile.  For QUANT8 `scale` is the tile's range
+// fp32 -> payload of a unit.  For QUANT8 `scale` is the tile's range
 // (tile_absmax); it is stored by thread 0.
-template <int MODE, bool FULL, bool NT>
+template <int MODE, class G, bool FULL, bool NT>
 __device__ __forceinline__ void store_payload(void *pay, float *sc, uint64_t e0, uint32_t len, float scale, const float *x)
 {
     using C = Codec<MODE>;
@@ -324,13 +386,13 @@ __device__ __forceinline__ void store_payload(void *pay, float *sc, uint64_t e0,
     if (FULL) {
         typename C::Raw *v = reinterpret_cast<typename C::Raw *>(static_cast<char *>(pay) + e0 * C::kBytes);
 #pragma unroll
-        for (int i = 0; i < kQuads; ++i) st<NT>(v + i * kThreads + threadIdx.x, C::encode(x + 4 * i, inv));
+        for (int i = 0; i < G::kQuads; ++i) st<NT>(v + i * G::kThreads + threadIdx.x, C::encode(x + 4 * i, inv));
     } else {
 #pragma unroll
-        for (int i = 0; i < kQuads; ++i)
+        for (int i = 0; i < G::kQuads; ++i)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const uint32_t idx = 4 * (i * kThreads + threadIdx.x) + e;
+                const uint32_t idx = 4 * (i * G::kThreads + threadIdx.x) + e;
                 if (idx < len) C::encode1(pay, e0 + idx, x[4 * i + e], inv);
             }
     }
@@ -339,19 +401,24 @@ __device__ __forceinline__ void store_payload(void *pay, float *sc, uint64_t e0,
 
 // What a receiver sees of a value it is sent: D(C(x)), without touching
 // memory (used by the fused schedule).
-template <int MODE>
+template <int MODE, class G>
 __device__ __forceinline__ void through_the_wire(float *x, float scale)
 {
     if (MODE == PIPESGD_TRUNC16) {
 #pragma unroll
-        for (int k = 0; k < kPerThread; ++k) x[k] = u2f(f2u(x[k]) & 0xffff0000u);
+        for (int k = 0; k < G::kPerThread; ++k) x[k] = u2f(f2u(x[k]) & 0xffff0000u);
     } else if (MODE == PIPESGD_QUANT8) {
         const float inv = quant_inverse(scale);
         const float step = scale / 127.0f;
 #pragma unroll
-        for (int k = 0; k < kPerThread; ++k) x[k] = static_cast<float>(quant_code(x[k], inv)) * step;
+        for (int k = 0; k < G::kPerThread; ++k) x[k] = static_cast<float>(quant_code(x[k], inv)) * step;
     }
 }
+
+// QUANT8 kernels that compute a range must see a whole tile per workgroup.
+template <int MODE, class G> struct RangeOk {
+    static constexpr bool value = MODE != PIPESGD_QUANT8 || G::kUnit == kTile;
+};
 
 // ---------------------------------------------------------------- kernels --
 
@@ -359,158 +426,175 @@ __device__ __forceinline__ void through_the_wire(float *x, float scale)
 //   HAS_IN = false: the first send.  C(g_r[chunk r]) -> slot r.
 //   HAS_IN = true : transmit-and-reduce round a.step.  D(slot r-1) + g_r -> C -> slot r.
 //   in_is_grad    : uncompressed round 0 reads the sender's gradient itself.
-template <int MODE, bool HAS_IN>
-__global__ __launch_bounds__(kThreads) void ring_hop_kernel(RingArgs a, BucketTable bt, int in_is_grad)
+template <int MODE, bool HAS_IN, class G, bool FULL>
+__device__ __forceinline__ void ring_hop_body(const RingArgs &a, const UnitRef &t, int r, int in_is_grad, float *red)
 {
-    __shared__ float red[4];
-    const int r = blockIdx.y;
-    const int chunk = HAS_IN ? mod_p(r - a.step - 1, a.p) : r;
-    const TileRef t = locate(bt, blockIdx.x, chunk);
-    if (t.len == 0) return;
-    const bool full = t.len == kTile;
-
-    float P[kPerThread];
-    if (full) load_f32_full<kNtGrad>(a.g[r] + t.elem0, P); else load_f32_tail(a.g[r] + t.elem0, t.len, P);
-
+    float P[G::kPerThread];
+    float x[G::kPerThread];
     if (HAS_IN) {
         const int src = mod_p(r - 1, a.p);
-        float x[kPerThread];
         if (MODE == PIPESGD_NONE && in_is_grad) {
-            if (full) load_f32_full<kNtGrad>(a.g[src] + t.elem0, x); else load_f32_tail(a.g[src] + t.elem0, t.len, x);
+            load_f32<G, FULL, kNtGrad>(a.g[src] + t.elem0, t.len, x);
         } else {
             const float scale_in = MODE == PIPESGD_QUANT8 ? a.sc[src][t.elem0 / kTile] : 0.0f;
-            if (full) load_payload<MODE, true, kNtPayIn>(a.pay[src], t.elem0, t.len, scale_in, x);
-            else      load_payload<MODE, false, false>(a.pay[src], t.elem0, t.len, scale_in, x);
+            load_payload<MODE, G, FULL, kNtPayIn>(a.pay[src], t.elem0, t.len, scale_in, x);
         }
-#pragma unroll
-        for (int k = 0; k < kPerThread; ++k) P[k] = x[k] + P[k];
     }
+    load_f32<G, FULL, kNtGrad>(a.g[r] + t.elem0, t.len, P);
+    if (HAS_IN) {
+#pragma unroll
+        for (int k = 0; k < G::kPerThread; ++k) P[k] = x[k] + P[k];
+    }
+    float scale = 0.0f;
+    if constexpr (MODE == PIPESGD_QUANT8) scale = tile_absmax<G>(P, red);
+    store_payload<MODE, G, FULL, kNtPayOut>(a.pay[r], a.sc[r], t.elem0, t.len, scale, P);
+}
 
-    const float scale = MODE == PIPESGD_QUANT8 ? tile_absmax(P, red) : 0.0f;
-    if (full) store_payload<MODE, true, kNtPayOut>(a.pay[r], a.sc[r], t.elem0, t.len, scale, P);
-    else      store_payload<MODE, false, false>(a.pay[r], a.sc[r], t.elem0, t.len, scale, P);
+template <int MODE, bool HAS_IN, class G>
+__global__ __launch_bounds__(G::kThreads) void ring_hop_kernel(RingArgs a, BucketTable bt, int in_is_grad)
+{
+    if constexpr (RangeOk<MODE, G>::value) {
+        __shared__ float red[G::kWaves];
+        const int r = blockIdx.y;
+        const int chunk = HAS_IN ? mod_p(r - a.step - 1, a.p) : r;
+        const UnitRef t = locate<G>(bt, blockIdx.x, chunk);
+        if (t.empty) return;
+        if (t.full) ring_hop_body<MODE, HAS_IN, G, true>(a, t, r, in_is_grad, red);
+        else        ring_hop_body<MODE, HAS_IN, G, false>(a, t, r, in_is_grad, red);
+    }
 }
 
 // One send-back round for every worker: byte copy of a chunk's payload (and
-// scales) from slot r-1 to slot r.
-template <int MODE>
-__global__ __launch_bounds__(kThreads) void ring_allgather_kernel(RingArgs a, BucketTable bt)
+// scales) from slot r-1 to slot r.  Geometry counts 16-byte vectors here:
+// a workgroup copies THREADS*QUADS of them.
+template <int MODE, class G>
+__global__ __launch_bounds__(G::kThreads) void ring_allgather_kernel(RingArgs a, BucketTable bt)
 {
     using C = Codec<MODE>;
-    const int r = blockIdx.y;
-    const int src = mod_p(r - 1, a.p);
-    const int chunk = mod_p(r - a.step, a.p);
-    const TileRef t = locate(bt, blockIdx.x, chunk);
-    if (t.len == 0) return;
-    const char *in = static_cast<const char *>(a.pay[src]) + t.elem0 * C::kBytes;
-    char *out = static_cast<char *>(a.pay[r]) + t.elem0 * C::kBytes;
-    if (t.len == kTile) {
-        constexpr int kVecs = kTile * C::kBytes / 16;          // 1024, 512 or 256 16-byte vectors
-        const u32x4 *vi = reinterpret_cast<const u32x4 *>(in);
-        u32x4 *vo = reinterpret_cast<u32x4 *>(out);
-        constexpr int kIter = kVecs / kThreads;
-        u32x4 tmp[kIter];
+    constexpr int kTileVecs = kTile * C::kBytes / 16;          // 1024, 512 or 256
+    constexpr int kUnitVecs = G::kThreads * G::kQuads;
+    if constexpr (kUnitVecs <= kTileVecs) {
+        constexpr int kSplit = kTileVecs / kUnitVecs;
+        constexpr int kUnitElems = kTile / kSplit;
+        const int r = blockIdx.y;
+        const int src = mod_p(r - 1, a.p);
+        const int chunk = mod_p(r - a.step, a.p);
+        const UnitRef t = locate<UnitOnly<kUnitElems>>(bt, blockIdx.x, chunk);
+        if (t.empty) return;
+        const char *in = static_cast<const char *>(a.pay[src]) + t.elem0 * C::kBytes;
+        char *out = static_cast<char *>(a.pay[r]) + t.elem0 * C::kBytes;
+        if (t.full) {
+            const u32x4 *vi = reinterpret_cast<const u32x4 *>(in);
+            u32x4 *vo = reinterpret_cast<u32x4 *>(out);
+            u32x4 tmp[G::kQuads];
 #pragma unroll
-        for (int i = 0; i < kIter; ++i) tmp[i] = ld<kNtPayIn>(vi + i * kThreads + threadIdx.x);
+            for (int i = 0; i < G::kQuads; ++i) tmp[i] = ld<kNtPayIn>(vi + i * G::kThreads + threadIdx.x);
 #pragma unroll
-        for (int i = 0; i < kIter; ++i) st<kNtPayOut>(vo + i * kThreads + threadIdx.x, tmp[i]);
-    } else {
-        const uint32_t bytes = t.len * C::kBytes;
-        for (uint32_t i = threadIdx.x; i < bytes; i += kThreads) out[i] = in[i];
+            for (int i = 0; i < G::kQuads; ++i) st<kNtPayOut>(vo + i * G::kThreads + threadIdx.x, tmp[i]);
+        } else {
+            const uint32_t bytes = t.len * C::kBytes;
+            for (uint32_t i = threadIdx.x; i < bytes; i += G::kThreads) out[i] = in[i];
+        }
+        if (MODE == PIPESGD_QUANT8 && threadIdx.x == 0 && t.elem0 % kTile == 0)
+            a.sc[r][t.elem0 / kTile] = a.sc[src][t.elem0 / kTile];
     }
-    if (MODE == PIPESGD_QUANT8 && threadIdx.x == 0) a.sc[r][t.elem0 / kTile] = a.sc[src][t.elem0 / kTile];
 }
 
-// The whole chain of one tile in registers (blockIdx.y = chunk c):
+// The whole chain of one unit in registers (blockIdx.y = chunk c):
 // P = g_c; for j = 1..p-1: P = D(C(P)) + g_{c+j}; every slot <- C(P).
-template <int MODE>
-__global__ __launch_bounds__(kThreads) void ring_fused_kernel(RingArgs a, BucketTable bt)
+template <int MODE, class G, bool FULL>
+__device__ __forceinline__ void ring_fused_body(const RingArgs &a, const UnitRef &t, int c, float (*red)[G::kWaves])
 {
-    __shared__ float red[2][4];
-    const int c = blockIdx.y;
-    const TileRef t = locate(bt, blockIdx.x, c);
-    if (t.len == 0) return;
-    const bool full = t.len == kTile;
     const int p = a.p;
-
-    float P[kPerThread], g[kPerThread];
-    if (full) load_f32_full<kNtGrad>(a.g[c] + t.elem0, P); else load_f32_tail(a.g[c] + t.elem0, t.len, P);
+    float P[G::kPerThread], g[G::kPerThread];
+    load_f32<G, FULL, kNtGrad>(a.g[c] + t.elem0, t.len, P);
     int flip = 0;
     for (int j = 1; j < p; ++j) {
         const int wkr = mod_p(c + j, p);
-        if (full) load_f32_full<kNtGrad>(a.g[wkr] + t.elem0, g); else load_f32_tail(a.g[wkr] + t.elem0, t.len, g);
+        load_f32<G, FULL, kNtGrad>(a.g[wkr] + t.elem0, t.len, g);
         float scale = 0.0f;
-        if (MODE == PIPESGD_QUANT8) { scale = tile_absmax(P, red[flip]); flip ^= 1; }
-        through_the_wire<MODE>(P, scale);
+        if constexpr (MODE == PIPESGD_QUANT8) { scale = tile_absmax<G>(P, red[flip]); flip ^= 1; }
+        through_the_wire<MODE, G>(P, scale);
 #pragma unroll
-        for (int k = 0; k < kPerThread; ++k) P[k] = P[k] + g[k];
+        for (int k = 0; k < G::kPerThread; ++k) P[k] = P[k] + g[k];
     }
     float scale = 0.0f;
-    if (MODE == PIPESGD_QUANT8) scale = tile_absmax(P, red[flip]);
-    for (int r = 0; r < p; ++r) {
-        if (full) store_payload<MODE, true, true>(a.pay[r], a.sc[r], t.elem0, t.len, scale, P);
-        else      store_payload<MODE, false, false>(a.pay[r], a.sc[r], t.elem0, t.len, scale, P);
+    if constexpr (MODE == PIPESGD_QUANT8) scale = tile_absmax<G>(P, red[flip]);
+    for (int r = 0; r < p; ++r) store_payload<MODE, G, FULL, true>(a.pay[r], a.sc[r], t.elem0, t.len, scale, P);
+}
+
+template <int MODE, class G>
+__global__ __launch_bounds__(G::kThreads) void ring_fused_kernel(RingArgs a, BucketTable bt)
+{
+    if constexpr (RangeOk<MODE, G>::value) {
+        __shared__ float red[2][G::kWaves];
+        const int c = blockIdx.y;
+        const UnitRef t = locate<G>(bt, blockIdx.x, c);
+        if (t.empty) return;
+        if (t.full) ring_fused_body<MODE, G, true>(a, t, c, red);
+        else        ring_fused_body<MODE, G, false>(a, t, c, red);
     }
 }
 
-// Stand-alone codec over a flat vector (blockIdx.x = tile).
-template <int MODE>
-__global__ __launch_bounds__(kThreads) void compress_kernel(const float *src, uint64_t n, void *pay, float *sc)
+// Stand-alone codec over a flat vector (blockIdx.x = unit).
+template <int MODE, class G, bool FULL>
+__device__ __forceinline__ void compress_body(const float *src, const UnitRef &t, void *pay, float *sc, float *red)
 {
-    __shared__ float red[4];
-    const uint64_t e0 = static_cast<uint64_t>(blockIdx.x) * kTile;
-    const uint64_t rem = n - e0;
-    const uint32_t len = rem < static_cast<uint64_t>(kTile) ? static_cast<uint32_t>(rem) : kTile;
-    float x[kPerThread];
-    if (len == kTile) load_f32_full<true>(src + e0, x); else load_f32_tail(src + e0, len, x);
-    const float scale = MODE == PIPESGD_QUANT8 ? tile_absmax(x, red) : 0.0f;
-    if (len == kTile) store_payload<MODE, true, false>(pay, sc, e0, len, scale, x);
-    else              store_payload<MODE, false, false>(pay, sc, e0, len, scale, x);
+    float x[G::kPerThread];
+    load_f32<G, FULL, true>(src + t.elem0, t.len, x);
+    float scale = 0.0f;
+    if constexpr (MODE == PIPESGD_QUANT8) scale = tile_absmax<G>(x, red);
+    store_payload<MODE, G, FULL, false>(pay, sc, t.elem0, t.len, scale, x);
 }
 
-template <int MODE>
-__global__ __launch_bounds__(kThreads) void decompress_kernel(const void *pay, const float *sc, uint64_t n, float *dst)
+template <int MODE, class G>
+__global__ __launch_bounds__(G::kThreads) void compress_kernel(const float *src, uint64_t n, void *pay, float *sc)
 {
-    const uint64_t e0 = static_cast<uint64_t>(blockIdx.x) * kTile;
-    const uint64_t rem = n - e0;
-    const uint32_t len = rem < static_cast<uint64_t>(kTile) ? static_cast<uint32_t>(rem) : kTile;
-    const float scale = MODE == PIPESGD_QUANT8 ? sc[blockIdx.x] : 0.0f;
-    float x[kPerThread];
-    if (len == kTile) { load_payload<MODE, true, true>(pay, e0, len, scale, x); store_f32_full<false>(dst + e0, x); }
-    else              { load_payload<MODE, false, false>(pay, e0, len, scale, x); store_f32_tail(dst + e0, len, x); }
+    if constexpr (RangeOk<MODE, G>::value) {
+        __shared__ float red[G::kWaves];
+        const UnitRef t = locate_flat<G>(n, blockIdx.x);
+        if (t.full) compress_body<MODE, G, true>(src, t, pay, sc, red);
+        else        compress_body<MODE, G, false>(src, t, pay, sc, red);
+    }
+}
+
+template <int MODE, class G, bool FULL>
+__device__ __forceinline__ void decompress_body(const void *pay, float scale, const UnitRef &t, float *dst)
+{
+    float x[G::kPerThread];
+    load_payload<MODE, G, FULL, true>(pay, t.elem0, t.len, scale, x);
+    store_f32<G, FULL, false>(dst + t.elem0, t.len, x);
+}
+
+template <int MODE, class G>
+__global__ __launch_bounds__(G::kThreads) void decompress_kernel(const void *pay, const float *sc, uint64_t n, float *dst)
+{
+    const UnitRef t = locate_flat<G>(n, blockIdx.x);
+    const float scale = MODE == PIPESGD_QUANT8 ? sc[t.elem0 / kTile] : 0.0f;
+    if (t.full) decompress_body<MODE, G, true>(pay, scale, t, dst);
+    else        decompress_body<MODE, G, false>(pay, scale, t, dst);
 }
 
 // Decompress + momentum-SGD step (Alg. 1 compute thread lines 4-5) for every
 // replica (blockIdx.y): reads the stale slot, v and w once, writes v and w once.
-template <int MODE, bool MOMENTUM>
-__global__ __launch_bounds__(kThreads) void update_kernel(UpdateArgs a)
+template <int MODE, bool MOMENTUM, class G, bool FULL>
+__device__ __forceinline__ void update_body(const UpdateArgs &a, const UnitRef &t, int r, float scale)
 {
-    const int r = blockIdx.y;
-    const uint64_t e0 = static_cast<uint64_t>(blockIdx.x) * kTile;
-    const uint64_t rem = a.n - e0;
-    const uint32_t len = rem < static_cast<uint64_t>(kTile) ? static_cast<uint32_t>(rem) : kTile;
-    const bool full = len == kTile;
-    const float scale = MODE == PIPESGD_QUANT8 ? a.sc[r][blockIdx.x] : 0.0f;
-    float *w = a.w[r] + e0;
-    float *v = MOMENTUM ? a.v[r] + e0 : nullptr;
+    float *w = a.w[r] + t.elem0;
+    float *v = MOMENTUM ? a.v[r] + t.elem0 : nullptr;
 
-    float g[kPerThread], wv[kPerThread], vv[kPerThread];
-    if (full) {
-        load_payload<MODE, true, kNtUpdate>(a.pay[r], e0, len, scale, g);
-        load_f32_full<kNtUpdate>(w, wv);
-        if (MOMENTUM) load_f32_full<kNtUpdate>(v, vv);
-    } else {
-        load_payload<MODE, false, false>(a.pay[r], e0, len, scale, g);
-        load_f32_tail(w, len, wv);
-        if (MOMENTUM) load_f32_tail(v, len, vv);
-    }
+    float g[G::kPerThread], wv[G::kPerThread], vv[G::kPerThread];
+    load_payload<MODE, G, FULL, kNtUpdate>(a.pay[r], t.elem0, t.len, scale, g);
+    load_f32<G, FULL, kNtUpdate>(w, t.len, wv);
+    if (MOMENTUM) load_f32<G, FULL, kNtUpdate>(v, t.len, vv);
+
     const float gs = a.grad_scale, m = a.momentum, neg_lr = -a.lr;
     if (gs != 1.0f) {
 #pragma unroll
-        for (int k = 0; k < kPerThread; ++k) g[k] = g[k] * gs;
+        for (int k = 0; k < G::kPerThread; ++k) g[k] = g[k] * gs;
     }
 #pragma unroll
-    for (int k = 0; k < kPerThread; ++k) {
+    for (int k = 0; k < G::kPerThread; ++k) {
         if (MOMENTUM) {
             vv[k] = fmaf(m, vv[k], g[k]);
             wv[k] = fmaf(neg_lr, vv[k], wv[k]);
@@ -518,20 +602,26 @@ __global__ __launch_bounds__(kThreads) void update_kernel(UpdateArgs a)
             wv[k] = fmaf(neg_lr, g[k], wv[k]);
         }
     }
-    if (full) {
-        if (MOMENTUM) store_f32_full<kNtUpdate>(v, vv);
-        store_f32_full<kNtUpdate>(w, wv);
-    } else {
-        if (MOMENTUM) store_f32_tail(v, len, vv);
-        store_f32_tail(w, len, wv);
-    }
+    if (MOMENTUM) store_f32<G, FULL, kNtUpdate>(v, t.len, vv);
+    store_f32<G, FULL, kNtUpdate>(w, t.len, wv);
+}
+
+template <int MODE, bool MOMENTUM, class G>
+__global__ __launch_bounds__(G::kThreads) void update_kernel(UpdateArgs a)
+{
+    const int r = blockIdx.y;
+    const UnitRef t = locate_flat<G>(a.n, blockIdx.x);
+    const float scale = MODE == PIPESGD_QUANT8 ? a.sc[r][t.elem0 / kTile] : 0.0f;
+    if (t.full) update_body<MODE, MOMENTUM, G, true>(a, t, r, scale);
+    else        update_body<MODE, MOMENTUM, G, false>(a, t, r, scale);
 }
 
 // Many tensor <-> packed-buffer copies in one launch.  The segment table is in
 // device memory; a block finds its segment by binary search on first_tile.
 template <bool TO_PACKED>
-__global__ __launch_bounds__(kThreads) void segment_copy_kernel(const pipesgd_segment *seg, uint32_t num)
+__global__ __launch_bounds__(256) void segment_copy_kernel(const pipesgd_segment *seg, uint32_t num)
 {
+    using G = Geo<256, 4>;
     const uint64_t tile = blockIdx.x;
     uint32_t lo = 0, hi = num;
     while (hi - lo > 1) {
@@ -548,21 +638,94 @@ __global__ __launch_bounds__(kThreads) void segment_copy_kernel(const pipesgd_se
     const bool vec = len == kTile &&
         ((reinterpret_cast<uintptr_t>(in) | reinterpret_cast<uintptr_t>(out)) & 15) == 0;
     if (vec) {
-        float x[kPerThread];
-        load_f32_full<true>(in, x);
-        store_f32_full<false>(out, x);
+        float x[G::kPerThread];
+        load_f32_full<G, true>(in, x);
+        store_f32<G, true, false>(out, kTile, x);
     } else {
-        for (uint32_t i = threadIdx.x; i < len; i += kThreads) out[i] = in[i];
+        for (uint32_t i = threadIdx.x; i < len; i += 256) out[i] = in[i];
     }
+}
+
+// --------------------------------------------------------- launch configs --
+
+enum KernelKind { kFirstSend = 0, kReduceScatter, kAllGather, kFused, kUpdate, kCompress, kDecompress, kNumKinds };
+
+struct LaunchConfig {
+    int threads, quads;
+    int lds_bytes;           // dynamic LDS reserved per workgroup: caps resident workgroups per CU
+};
+
+// Defaults from sweeps on MI355X inside the whole iteration loop (NONE at 25.6M
+// elements per worker, TRUNC16 at 61M, QUANT8 at 138M; p = 4).  The update wants
+// small workgroups (one quad per thread) and, for the 16-byte-per-quad streams,
+// at most two resident workgroups' worth of LDS reservation per CU; the hop
+// kernels are nearly flat across geometries.  [kind][mode]
+LaunchConfig g_cfg[kNumKinds][3] = {
+    /* first send     */ {{256, 4, 0}, {128, 2, 0}, {512, 2, 32768}},
+    /* reduce-scatter */ {{128, 2, 0}, {128, 2, 0}, {256, 4, 32768}},
+    /* all-gather     */ {{128, 2, 0}, {256, 2, 0}, {256, 1, 0}},
+    /* fused          */ {{256, 4, 0}, {256, 4, 0}, {256, 4, 0}},
+    /* update         */ {{256, 1, 65536}, {256, 1, 65536}, {256, 1, 0}},
+    /* compress       */ {{256, 4, 0}, {256, 4, 0}, {256, 4, 0}},
+    /* decompress     */ {{256, 4, 0}, {256, 4, 0}, {256, 4, 0}},
+};
+
+constexpr int kMaxLds = 159 * 1024;        // a CU has 160 KiB; leave room for the kernels' own few bytes
+
+#define PIPESGD_FOR_EACH_GEO(X) X(64, 4) X(128, 2) X(128, 4) X(256, 1) X(256, 2) X(256, 4) X(512, 1) X(512, 2) X(1024, 1)
+
+inline bool geo_known(int threads, int quads)
+{
+#define X(T, Q) if (threads == T && quads == Q) return true;
+    PIPESGD_FOR_EACH_GEO(X)
+#undef X
+    return false;
+}
+
+// Does this geometry work for this kernel kind and mode?
+bool config_ok(int kind, int mode, const LaunchConfig &c)
+{
+    if (!geo_known(c.threads, c.quads) || c.lds_bytes < 0 || c.lds_bytes > kMaxLds) return false;
+    const int unit_quads = c.threads * c.quads;
+    if (kind == kAllGather) {
+        const int tile_vecs = kTile * (mode == PIPESGD_NONE ? 4 : mode == PIPESGD_TRUNC16 ? 2 : 1) / 16;
+        return unit_quads <= tile_vecs;
+    }
+    const bool needs_range = mode == PIPESGD_QUANT8 && (kind == kFirstSend || kind == kReduceScatter || kind == kFused || kind == kCompress);
+    return !needs_range || unit_quads == kTileQuads;
+}
+
+// Kernels that reserve more than 64 KiB of dynamic LDS must say so once per device.
+template <typename K>
+int allow_lds(K kernel, int lds_bytes, std::atomic<uint32_t> &done_mask)
+{
+    if (lds_bytes <= 64 * 1024) return PIPESGD_OK;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return PIPESGD_ERR_HIP;
+    const uint32_t bit = 1u << (dev & 31);
+    if (done_mask.load(std::memory_order_acquire) & bit) return PIPESGD_OK;
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLds) != hipSuccess)
+        return PIPESGD_ERR_HIP;
+    done_mask.fetch_or(bit, std::memory_order_release);
+    return PIPESGD_OK;
+}
+
+template <typename K, typename... Args>
+int launch(K kernel, dim3 grid, int threads, int lds_bytes, hipStream_t s, std::atomic<uint32_t> &done_mask, Args... args)
+{
+    const int rc = allow_lds(kernel, lds_bytes, done_mask);
+    if (rc != PIPESGD_OK) return rc;
+    hipLaunchKernelGGL(kernel, grid, dim3(threads), lds_bytes, s, args...);
+    return hipGetLastError() == hipSuccess ? PIPESGD_OK : PIPESGD_ERR_HIP;
 }
 
 // ------------------------------------------------------------ host helpers --
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 inline bool mode_ok(int mode) { return mode == PIPESGD_NONE || mode == PIPESGD_TRUNC16 || mode == PIPESGD_QUANT8; }
-inline int launch_status() { return hipGetLastError() == hipSuccess ? PIPESGD_OK : PIPESGD_ERR_HIP; }
 
-// Validates a ring and turns it into kernel arguments.  total_slots = grid.x.
+// Validates a ring and turns it into kernel arguments.  total_slots = tile
+// slots of one ring block, summed over buckets.
 int prepare_ring(const pipesgd_ring *ring, RingArgs &ra, BucketTable &bt, uint64_t &total_slots)
 {
     if (!ring) return PIPESGD_ERR_ARG;
@@ -603,7 +766,7 @@ int prepare_ring(const pipesgd_ring *ring, RingArgs &ra, BucketTable &bt, uint64
         bt.start[i] = b[i].start;
         bt.n[i] = b[i].n;
         slots += ce_tiles;
-        if (slots > 0x7fffffffull) return PIPESGD_ERR_CAPACITY;
+        if (slots > 0x07ffffffull) return PIPESGD_ERR_CAPACITY;      // x 8 units per tile still fits gridDim.x
     }
     for (uint32_t i = nb; i < static_cast<uint32_t>(kMaxB); ++i) {
         bt.slot_prefix[i] = static_cast<uint32_t>(slots);
@@ -615,66 +778,151 @@ int prepare_ring(const pipesgd_ring *ring, RingArgs &ra, BucketTable &bt, uint64
     return PIPESGD_OK;
 }
 
-template <int MODE>
-int launch_first_send(const RingArgs &ra, const BucketTable &bt, uint64_t slots, hipStream_t s)
+// ---- per-kind dispatch over (mode, geometry) ----
+
+#define PIPESGD_MODE_SWITCH(mode, CALL)                      \
+    switch (mode) {                                          \
+    case PIPESGD_NONE:    CALL(PIPESGD_NONE) break;          \
+    case PIPESGD_TRUNC16: CALL(PIPESGD_TRUNC16) break;       \
+    default:              CALL(PIPESGD_QUANT8) break;        \
+    }
+
+template <int MODE, bool HAS_IN>
+int launch_hop(const LaunchConfig &c, const RingArgs &ra, const BucketTable &bt, uint64_t slots, int in_is_grad, hipStream_t s)
 {
-    hipLaunchKernelGGL((ring_hop_kernel<MODE, false>), dim3(static_cast<uint32_t>(slots), ra.p), dim3(kThreads), 0, s,
-                       ra, bt, 0);
-    return launch_status();
-}
-template <int MODE>
-int launch_rs(const RingArgs &ra, const BucketTable &bt, uint64_t slots, hipStream_t s)
-{
-    hipLaunchKernelGGL((ring_hop_kernel<MODE, true>), dim3(static_cast<uint32_t>(slots), ra.p), dim3(kThreads), 0, s,
-                       ra, bt, (MODE == PIPESGD_NONE && ra.step == 0) ? 1 : 0);
-    return launch_status();
-}
-template <int MODE>
-int launch_ag(const RingArgs &ra, const BucketTable &bt, uint64_t slots, hipStream_t s)
-{
-    hipLaunchKernelGGL((ring_allgather_kernel<MODE>), dim3(static_cast<uint32_t>(slots), ra.p), dim3(kThreads), 0, s,
-                       ra, bt);
-    return launch_status();
-}
-template <int MODE>
-int launch_fused(const RingArgs &ra, const BucketTable &bt, uint64_t slots, hipStream_t s)
-{
-    hipLaunchKernelGGL((ring_fused_kernel<MODE>), dim3(static_cast<uint32_t>(slots), ra.p), dim3(kThreads), 0, s,
-                       ra, bt);
-    return launch_status();
+#define X(T, Q)                                                                                                  \
+    if (c.threads == T && c.quads == Q) {                                                                        \
+        static std::atomic<uint32_t> done{0};                                                                    \
+        using G = Geo<T, Q>;                                                                                     \
+        return launch(ring_hop_kernel<MODE, HAS_IN, G>, dim3(static_cast<uint32_t>(slots * G::kSplit), ra.p), T, \
+                      c.lds_bytes, s, done, ra, bt, in_is_grad);                                                 \
+    }
+    PIPESGD_FOR_EACH_GEO(X)
+#undef X
+    return PIPESGD_ERR_ARG;
 }
 
-#define PIPESGD_DISPATCH_MODE(mode, fn, ...)                                   \
-    ((mode) == PIPESGD_NONE      ? fn<PIPESGD_NONE>(__VA_ARGS__)               \
-     : (mode) == PIPESGD_TRUNC16 ? fn<PIPESGD_TRUNC16>(__VA_ARGS__)            \
-                                 : fn<PIPESGD_QUANT8>(__VA_ARGS__))
+template <int MODE>
+int launch_allgather(const LaunchConfig &c, const RingArgs &ra, const BucketTable &bt, uint64_t slots, hipStream_t s)
+{
+    constexpr int kTileVecs = kTile * Codec<MODE>::kBytes / 16;
+#define X(T, Q)                                                                                                  \
+    if (c.threads == T && c.quads == Q) {                                                                        \
+        if constexpr (T * Q <= kTileVecs) {                                                                      \
+            static std::atomic<uint32_t> done{0};                                                                \
+            constexpr int kSplit = kTileVecs / (T * Q);                                                          \
+            return launch(ring_allgather_kernel<MODE, Geo<T, Q>>, dim3(static_cast<uint32_t>(slots * kSplit), ra.p), T, \
+                          c.lds_bytes, s, done, ra, bt);                                                         \
+        }                                                                                                        \
+    }
+    PIPESGD_FOR_EACH_GEO(X)
+#undef X
+    return PIPESGD_ERR_ARG;
+}
+
+template <int MODE>
+int launch_fused(const LaunchConfig &c, const RingArgs &ra, const BucketTable &bt, uint64_t slots, hipStream_t s)
+{
+#define X(T, Q)                                                                                                  \
+    if (c.threads == T && c.quads == Q) {                                                                        \
+        static std::atomic<uint32_t> done{0};                                                                    \
+        using G = Geo<T, Q>;                                                                                     \
+        return launch(ring_fused_kernel<MODE, G>, dim3(static_cast<uint32_t>(slots * G::kSplit), ra.p), T,       \
+                      c.lds_bytes, s, done, ra, bt);                                                             \
+    }
+    PIPESGD_FOR_EACH_GEO(X)
+#undef X
+    return PIPESGD_ERR_ARG;
+}
+
+template <int MODE>
+int launch_compress(const LaunchConfig &c, const float *src, uint64_t n, void *pay, float *sc, hipStream_t s)
+{
+#define X(T, Q)                                                                                                  \
+    if (c.threads == T && c.quads == Q) {                                                                        \
+        static std::atomic<uint32_t> done{0};                                                                    \
+        using G = Geo<T, Q>;                                                                                     \
+        const uint64_t units = (n + G::kUnit - 1) / G::kUnit;                                                    \
+        if (units > 0x7fffffffull) return PIPESGD_ERR_CAPACITY;                                                  \
+        return launch(compress_kernel<MODE, G>, dim3(static_cast<uint32_t>(units)), T, c.lds_bytes, s, done,     \
+                      src, n, pay, sc);                                                                          \
+    }
+    PIPESGD_FOR_EACH_GEO(X)
+#undef X
+    return PIPESGD_ERR_ARG;
+}
+
+template <int MODE>
+int launch_decompress(const LaunchConfig &c, const void *pay, const float *sc, uint64_t n, float *dst, hipStream_t s)
+{
+#define X(T, Q)                                                                                                  \
+    if (c.threads == T && c.quads == Q) {                                                                        \
+        static std::atomic<uint32_t> done{0};                                                                    \
+        using G = Geo<T, Q>;                                                                                     \
+        const uint64_t units = (n + G::kUnit - 1) / G::kUnit;                                                    \
+        if (units > 0x7fffffffull) return PIPESGD_ERR_CAPACITY;                                                  \
+        return launch(decompress_kernel<MODE, G>, dim3(static_cast<uint32_t>(units)), T, c.lds_bytes, s, done,   \
+                      pay, sc, n, dst);                                                                          \
+    }
+    PIPESGD_FOR_EACH_GEO(X)
+#undef X
+    return PIPESGD_ERR_ARG;
+}
+
+template <int MODE, bool MOMENTUM>
+int launch_update(const LaunchConfig &c, const UpdateArgs &ua, int replicas, hipStream_t s)
+{
+#define X(T, Q)                                                                                                  \
+    if (c.threads == T && c.quads == Q) {                                                                        \
+        static std::atomic<uint32_t> done{0};                                                                    \
+        using G = Geo<T, Q>;                                                                                     \
+        const uint64_t units = (ua.n + G::kUnit - 1) / G::kUnit;                                                 \
+        if (units > 0x7fffffffull) return PIPESGD_ERR_CAPACITY;                                                  \
+        return launch(update_kernel<MODE, MOMENTUM, G>, dim3(static_cast<uint32_t>(units), replicas), T,         \
+                      c.lds_bytes, s, done, ua);                                                                 \
+    }
+    PIPESGD_FOR_EACH_GEO(X)
+#undef X
+    return PIPESGD_ERR_ARG;
+}
 
 int first_send_impl(int mode, const RingArgs &ra, const BucketTable &bt, uint64_t slots, hipStream_t s)
 {
     // uncompressed, p > 1: the first round reads the sender's gradient in place
     if (slots == 0 || (mode == PIPESGD_NONE && ra.p > 1)) return PIPESGD_OK;
-    return PIPESGD_DISPATCH_MODE(mode, launch_first_send, ra, bt, slots, s);
+    const LaunchConfig c = g_cfg[kFirstSend][mode];
+#define CALL(M) return launch_hop<M, false>(c, ra, bt, slots, 0, s);
+    PIPESGD_MODE_SWITCH(mode, CALL)
+#undef CALL
+    return PIPESGD_ERR_MODE;
 }
 
-template <int MODE>
-int launch_compress(const float *src, uint64_t n, void *pay, float *sc, uint64_t tiles, hipStream_t s)
+int rs_impl(int mode, const RingArgs &ra, const BucketTable &bt, uint64_t slots, hipStream_t s)
 {
-    hipLaunchKernelGGL((compress_kernel<MODE>), dim3(static_cast<uint32_t>(tiles)), dim3(kThreads), 0, s, src, n, pay, sc);
-    return launch_status();
+    const LaunchConfig c = g_cfg[kReduceScatter][mode];
+    const int in_is_grad = (mode == PIPESGD_NONE && ra.step == 0) ? 1 : 0;
+#define CALL(M) return launch_hop<M, true>(c, ra, bt, slots, in_is_grad, s);
+    PIPESGD_MODE_SWITCH(mode, CALL)
+#undef CALL
+    return PIPESGD_ERR_MODE;
 }
-template <int MODE>
-int launch_decompress(const void *pay, const float *sc, uint64_t n, float *dst, uint64_t tiles, hipStream_t s)
+
+int ag_impl(int mode, const RingArgs &ra, const BucketTable &bt, uint64_t slots, hipStream_t s)
 {
-    hipLaunchKernelGGL((decompress_kernel<MODE>), dim3(static_cast<uint32_t>(tiles)), dim3(kThreads), 0, s, pay, sc, n, dst);
-    return launch_status();
+    const LaunchConfig c = g_cfg[kAllGather][mode];
+#define CALL(M) return launch_allgather<M>(c, ra, bt, slots, s);
+    PIPESGD_MODE_SWITCH(mode, CALL)
+#undef CALL
+    return PIPESGD_ERR_MODE;
 }
-template <int MODE>
-int launch_update(const UpdateArgs &ua, int replicas, uint64_t tiles, bool momentum, hipStream_t s)
+
+int fused_impl(int mode, const RingArgs &ra, const BucketTable &bt, uint64_t slots, hipStream_t s)
 {
-    const dim3 grid(static_cast<uint32_t>(tiles), replicas);
-    if (momentum) hipLaunchKernelGGL((update_kernel<MODE, true>), grid, dim3(kThreads), 0, s, ua);
-    else          hipLaunchKernelGGL((update_kernel<MODE, false>), grid, dim3(kThreads), 0, s, ua);
-    return launch_status();
+    const LaunchConfig c = g_cfg[kFused][mode];
+#define CALL(M) return launch_fused<M>(c, ra, bt, slots, s);
+    PIPESGD_MODE_SWITCH(mode, CALL)
+#undef CALL
+    return PIPESGD_ERR_MODE;
 }
 
 }  // namespace
@@ -683,15 +931,38 @@ int launch_update(const UpdateArgs &ua, int replicas, uint64_t tiles, bool momen
 
 extern "C" {
 
+int pipesgd_set_launch_config(int kernel, int mode, int threads, int quads, int lds_bytes)
+{
+    if (kernel < 0 || kernel >= kNumKinds) return PIPESGD_ERR_ARG;
+    if (!mode_ok(mode)) return PIPESGD_ERR_MODE;
+    const LaunchConfig c = {threads, quads, lds_bytes};
+    if (!config_ok(kernel, mode, c)) return PIPESGD_ERR_ARG;
+    g_cfg[kernel][mode] = c;
+    return PIPESGD_OK;
+}
+
+int pipesgd_get_launch_config(int kernel, int mode, int *threads, int *quads, int *lds_bytes)
+{
+    if (kernel < 0 || kernel >= kNumKinds || !threads || !quads || !lds_bytes) return PIPESGD_ERR_ARG;
+    if (!mode_ok(mode)) return PIPESGD_ERR_MODE;
+    *threads = g_cfg[kernel][mode].threads;
+    *quads = g_cfg[kernel][mode].quads;
+    *lds_bytes = g_cfg[kernel][mode].lds_bytes;
+    return PIPESGD_OK;
+}
+
 int pipesgd_compress(int mode, const float *src, uint64_t n, void *payload, float *scales, void *stream)
 {
     if (!mode_ok(mode)) return PIPESGD_ERR_MODE;
     if (n == 0) return PIPESGD_OK;
     if (!src || !payload || (mode == PIPESGD_QUANT8 && !scales)) return PIPESGD_ERR_ARG;
     if (!aligned16(src) || !aligned16(payload) || (mode == PIPESGD_QUANT8 && !aligned16(scales))) return PIPESGD_ERR_ALIGN;
-    const uint64_t tiles = (n + kTile - 1) / kTile;
-    if (tiles > 0x7fffffffull) return PIPESGD_ERR_CAPACITY;
-    return PIPESGD_DISPATCH_MODE(mode, launch_compress, src, n, payload, scales, tiles, static_cast<hipStream_t>(stream));
+    const LaunchConfig c = g_cfg[kCompress][mode];
+    hipStream_t s = static_cast<hipStream_t>(stream);
+#define CALL(M) return launch_compress<M>(c, src, n, payload, scales, s);
+    PIPESGD_MODE_SWITCH(mode, CALL)
+#undef CALL
+    return PIPESGD_ERR_MODE;
 }
 
 int pipesgd_decompress(int mode, const void *payload, const float *scales, uint64_t n, float *dst, void *stream)
@@ -700,9 +971,12 @@ int pipesgd_decompress(int mode, const void *payload, const float *scales, uint6
     if (n == 0) return PIPESGD_OK;
     if (!dst || !payload || (mode == PIPESGD_QUANT8 && !scales)) return PIPESGD_ERR_ARG;
     if (!aligned16(dst) || !aligned16(payload) || (mode == PIPESGD_QUANT8 && !aligned16(scales))) return PIPESGD_ERR_ALIGN;
-    const uint64_t tiles = (n + kTile - 1) / kTile;
-    if (tiles > 0x7fffffffull) return PIPESGD_ERR_CAPACITY;
-    return PIPESGD_DISPATCH_MODE(mode, launch_decompress, payload, scales, n, dst, tiles, static_cast<hipStream_t>(stream));
+    const LaunchConfig c = g_cfg[kDecompress][mode];
+    hipStream_t s = static_cast<hipStream_t>(stream);
+#define CALL(M) return launch_decompress<M>(c, payload, scales, n, dst, s);
+    PIPESGD_MODE_SWITCH(mode, CALL)
+#undef CALL
+    return PIPESGD_ERR_MODE;
 }
 
 int pipesgd_ring_first_send(const pipesgd_ring *ring, void *stream)
@@ -721,7 +995,7 @@ int pipesgd_ring_reduce_scatter_step(const pipesgd_ring *ring, int step, void *s
     if (step < 0 || step > ring->workers - 2) return PIPESGD_ERR_ARG;
     if (slots == 0) return PIPESGD_OK;
     ra.step = step;
-    return PIPESGD_DISPATCH_MODE(ring->mode, launch_rs, ra, bt, slots, static_cast<hipStream_t>(stream));
+    return rs_impl(ring->mode, ra, bt, slots, static_cast<hipStream_t>(stream));
 }
 
 int pipesgd_ring_allgather_step(const pipesgd_ring *ring, int step, void *stream)
@@ -732,7 +1006,7 @@ int pipesgd_ring_allgather_step(const pipesgd_ring *ring, int step, void *stream
     if (step < 0 || step > ring->workers - 2) return PIPESGD_ERR_ARG;
     if (slots == 0) return PIPESGD_OK;
     ra.step = step;
-    return PIPESGD_DISPATCH_MODE(ring->mode, launch_ag, ra, bt, slots, static_cast<hipStream_t>(stream));
+    return ag_impl(ring->mode, ra, bt, slots, static_cast<hipStream_t>(stream));
 }
 
 int pipesgd_allreduce_sim(const pipesgd_ring *ring, int schedule, void *stream)
@@ -744,15 +1018,15 @@ int pipesgd_allreduce_sim(const pipesgd_ring *ring, int schedule, void *stream)
     if (slots == 0) return PIPESGD_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int mode = ring->mode, p = ring->workers;
-    if (schedule == PIPESGD_FUSED) return PIPESGD_DISPATCH_MODE(mode, launch_fused, ra, bt, slots, s);
+    if (schedule == PIPESGD_FUSED) return fused_impl(mode, ra, bt, slots, s);
     rc = first_send_impl(mode, ra, bt, slots, s);
     for (int step = 0; rc == PIPESGD_OK && step <= p - 2; ++step) {
         ra.step = step;
-        rc = PIPESGD_DISPATCH_MODE(mode, launch_rs, ra, bt, slots, s);
+        rc = rs_impl(mode, ra, bt, slots, s);
     }
     for (int step = 0; rc == PIPESGD_OK && step <= p - 2; ++step) {
         ra.step = step;
-        rc = PIPESGD_DISPATCH_MODE(mode, launch_ag, ra, bt, slots, s);
+        rc = ag_impl(mode, ra, bt, slots, s);
     }
     return rc;
 }
@@ -783,9 +1057,12 @@ int pipesgd_apply_update_multi(int mode, int replicas, const void *const *g_sum_
         ua.v[r] = mom ? v[r] : nullptr;
     }
     ua.n = n; ua.lr = lr; ua.momentum = momentum; ua.grad_scale = grad_scale;
-    const uint64_t tiles = (n + kTile - 1) / kTile;
-    if (tiles > 0x7fffffffull) return PIPESGD_ERR_CAPACITY;
-    return PIPESGD_DISPATCH_MODE(mode, launch_update, ua, replicas, tiles, mom, static_cast<hipStream_t>(stream));
+    const LaunchConfig c = g_cfg[kUpdate][mode];
+    hipStream_t s = static_cast<hipStream_t>(stream);
+#define CALL(M) return mom ? launch_update<M, true>(c, ua, replicas, s) : launch_update<M, false>(c, ua, replicas, s);
+    PIPESGD_MODE_SWITCH(mode, CALL)
+#undef CALL
+    return PIPESGD_ERR_MODE;
 }
 
 int pipesgd_apply_update(int mode, const void *g_sum_c, const float *scales, uint64_t n,
@@ -808,9 +1085,9 @@ static int segment_copy(const pipesgd_segment *segments, uint64_t num, uint64_t 
     if (num > 0x7fffffffull || total_tiles > 0x7fffffffull) return PIPESGD_ERR_CAPACITY;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const dim3 grid(static_cast<uint32_t>(total_tiles));
-    if (to_packed) hipLaunchKernelGGL((segment_copy_kernel<true>), grid, dim3(kThreads), 0, s, segments, static_cast<uint32_t>(num));
-    else           hipLaunchKernelGGL((segment_copy_kernel<false>), grid, dim3(kThreads), 0, s, segments, static_cast<uint32_t>(num));
-    return launch_status();
+    if (to_packed) hipLaunchKernelGGL((segment_copy_kernel<true>), grid, dim3(256), 0, s, segments, static_cast<uint32_t>(num));
+    else           hipLaunchKernelGGL((segment_copy_kernel<false>), grid, dim3(256), 0, s, segments, static_cast<uint32_t>(num));
+    return hipGetLastError() == hipSuccess ? PIPESGD_OK : PIPESGD_ERR_HIP;
 }
 
 int pipesgd_pack(const pipesgd_segment *segments, uint64_t num, uint64_t total_tiles, void *stream)

@@ -1,0 +1,83 @@
+"""GPU parity at the full sizes of the workload list, in the launch
+configuration bench.py times (p = 4, stepwise schedule, all replicas updated in
+one launch, width 2).  The scalar oracle finishes one full-size iteration in a
+second or two, so every output element is compared, not a sample.
+"""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+from paper_1811_03619_amd import binding as B
+from paper_1811_03619_amd import workloads as W
+from paper_1811_03619_amd.pipeline import PipeSgdSim
+
+from gpu_util import assert_bits_equal, assert_fp32_close_then_exact, sync
+
+pytestmark = pytest.mark.gpu
+
+
+def full_config_inputs(cfg, p, seed):
+    specs = W.config_tensors(cfg)
+    numels = [s.numel for s in specs]
+    if cfg == 5:
+        buckets, offs, n = B.bucket_plan(numels, 1 << 20)
+    else:
+        buckets, offs, n = None, list(np.cumsum([0] + numels[:-1])), int(sum(numels))
+    grads = []
+    for r in range(p):
+        flat = np.zeros(n, dtype=np.float32)
+        for t, o in zip(W.gradient_tensors(cfg, r, seed), offs):
+            flat[o:o + t.size] = t
+        grads.append(flat)
+    return buckets, n, grads
+
+
+@pytest.mark.parametrize("cfg,mode,schedule", [
+    (3, B.TRUNC16, B.STEPWISE),     # the headline configuration
+    (3, B.TRUNC16, B.FUSED),
+    (4, B.QUANT8, B.STEPWISE),
+    (5, B.NONE, B.STEPWISE),
+    (5, B.TRUNC16, B.STEPWISE),
+    (5, B.TRUNC16, B.FUSED),
+])
+def test_full_size_two_iterations(orc, cfg, mode, schedule):
+    p, lr, m = 4, 0.01, 0.9
+    t0 = time.time()
+    buckets, n, grads = full_config_inputs(cfg, p, seed=1)
+    w0 = W.gaussian(n, 0.05, 1, (cfg, 99, 0, 0))
+    print(f"[cfg{cfg} mode{mode} sched{schedule}] n={n} inputs in {time.time() - t0:.1f}s", flush=True)
+
+    sim = PipeSgdSim(mode, p, n, lr, m, 1.0, 2, buckets, schedule)
+    sim.set_gradients(grads)
+    sim.set_model(w0)
+    sim.iteration()            # t=1: AllReduce -> slot 1, update from the zero slot
+    sim.iteration()            # t=2: AllReduce -> slot 0, update from slot 1
+    sync()
+
+    t0 = time.time()
+    A = orc.allreduce_bucketed(mode, grads, buckets) if buckets else orc.allreduce(mode, grads)
+    w_ref, v_ref = w0.copy(), np.zeros(n, np.float32)
+    orc.sgd_update(mode, A[0][0], A[0][1], w_ref, v_ref, lr, m, 1.0)     # the t=2 update (t=1's is a no-op)
+    print(f"[cfg{cfg}] oracle in {time.time() - t0:.1f}s", flush=True)
+
+    for slot in (0, 1):
+        pay, sc = sim.result(0, slot)
+        if mode == B.NONE:
+            assert_fp32_close_then_exact(pay, A[0][0], f"sum slot {slot}")
+        else:
+            assert_bits_equal(pay, A[0][0], f"payload slot {slot}")
+        if mode == B.QUANT8:
+            assert_bits_equal(sc, A[0][1], f"scales slot {slot}")
+        for r in range(1, p):                                   # replicas: identical bytes (compared on the device)
+            assert torch.equal(sim.slots[slot][r], sim.slots[slot][0]), (slot, r)
+            if mode == B.QUANT8:
+                assert torch.equal(sim.slot_scales[slot][r], sim.slot_scales[slot][0]), (slot, r)
+    # the oracle's replicas are identical by its own pins; compare every GPU replica to the one reference
+    assert_fp32_close_then_exact(sim.model(0), w_ref, "w")
+    assert_fp32_close_then_exact(sim.velocity(0), v_ref, "v")
+    for r in range(1, p):
+        assert torch.equal(sim.w[r], sim.w[0]) and torch.equal(sim.v[r], sim.v[0]), r
+    for r in range(p):
+        assert torch.equal(sim.g_local[r].cpu(), torch.from_numpy(grads[r])), "gradients must not be modified"

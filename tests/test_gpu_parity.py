@@ -408,3 +408,80 @@ def test_scaled_resnet_bucketed_pipeline(orc, mode, schedule):
     for r in range(p):
         assert_fp32_close_then_exact(sim.model(r), ws_ref[r], f"w r={r}")
         assert_fp32_close_then_exact(sim.velocity(r), vs_ref[r], f"v r={r}")
+
+
+# ------------------------------------------------- every launch geometry --
+
+GEOS = [(64, 4), (128, 2), (128, 4), (256, 1), (256, 2), (256, 4), (512, 1), (512, 2), (1024, 1)]
+KINDS = [B.K_FIRST_SEND, B.K_REDUCE_SCATTER, B.K_ALLGATHER, B.K_FUSED, B.K_UPDATE, B.K_COMPRESS, B.K_DECOMPRESS]
+
+
+@pytest.fixture
+def restore_launch_configs():
+    saved = {(k, m): B.get_launch_config(k, m) for k in KINDS for m in MODES}
+    yield
+    for (k, m), c in saved.items():
+        B.set_launch_config(k, m, *c)
+
+
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("geo", GEOS)
+@pytest.mark.parametrize("lds", [0, 48 * 1024, 159 * 1024])
+def test_every_launch_geometry_gives_the_same_bits(orc, restore_launch_configs, mode, geo, lds):
+    # results must not depend on the tuning table: run the whole path with one
+    # geometry for every kernel family (where that family supports it) on a
+    # ragged, bucketed input and compare with the oracle
+    used = []
+    for kind in KINDS:
+        rc = B.lib().pipesgd_set_launch_config(kind, mode, geo[0], geo[1], lds)
+        assert rc in (0, -1)
+        used.append(rc == 0)
+    if not any(used):
+        pytest.skip("geometry not applicable to this mode")
+    p = 3
+    numels = [5000, 4096, 12289, 77, 1, 30000]
+    buckets, offs, N = B.bucket_plan(numels, 20000)
+    tens = [[special_values(ne, 7 * r + ti + 1) if ne > 100 else W.gaussian(ne, 1.0, r, (0, ti, 0, 0))
+             for ti, ne in enumerate(numels)] for r in range(p)]
+    packed = [orc.pack(t, offs, N) for t in tens]
+    want = orc.allreduce_bucketed(mode, packed, buckets)
+    for schedule in (B.STEPWISE, B.FUSED):
+        g_dev, slots, scs = ring_buffers(mode, packed, poison=False)
+        ring = B.make_ring(mode, N, g_dev, slots, scs if mode == B.QUANT8 else None, buckets)
+        B.allreduce_sim(ring, schedule)
+        sync()
+        for r in range(p):
+            assert_bits_equal(down(slots[r], mode), want[r][0], f"payload r={r} schedule={schedule}")
+            if mode == B.QUANT8:
+                assert_bits_equal(down(scs[r]), want[r][1], f"scales r={r}")
+    # codec + update on a flat ragged vector
+    n = 4096 * 3 + 1234
+    x = special_values(n, 99)
+    wp, ws = orc.compress(mode, x)
+    pay, sc = pay_buf(mode, n), dev_zeros(B.num_scales(mode, n), fill=-1.0)
+    B.compress(mode, up(x), n, pay, sc if mode == B.QUANT8 else None)
+    out = dev_zeros(n, fill=float("nan"))
+    B.decompress(mode, pay, sc if mode == B.QUANT8 else None, n, out)
+    w0, v0 = W.gaussian(n, 1.0, 43), W.gaussian(n, 0.1, 45)
+    w, v = up(w0), up(v0)
+    B.apply_update(mode, pay, sc if mode == B.QUANT8 else None, n, w, v, 0.01, 0.9, 1.0)
+    sync()
+    assert_bits_equal(down(pay, mode), wp, "payload")
+    if mode == B.QUANT8:
+        assert_bits_equal(down(sc), ws, "scales")
+    assert_bits_equal(down(out), orc.decompress(mode, wp, ws), "decompressed")
+    orc.sgd_update(mode, wp, ws, w0, v0, 0.01, 0.9, 1.0)
+    assert_fp32_close_then_exact(down(w), w0, "w")
+    assert_fp32_close_then_exact(down(v), v0, "v")
+
+
+def test_launch_config_validation():
+    L = B.lib()
+    assert L.pipesgd_set_launch_config(99, 0, 256, 4, 0) == -1
+    assert L.pipesgd_set_launch_config(B.K_UPDATE, 5, 256, 4, 0) == -3
+    assert L.pipesgd_set_launch_config(B.K_UPDATE, 0, 100, 4, 0) == -1           # unknown geometry
+    assert L.pipesgd_set_launch_config(B.K_UPDATE, 0, 256, 4, 200 * 1024) == -1  # more LDS than a CU has
+    assert L.pipesgd_set_launch_config(B.K_REDUCE_SCATTER, B.QUANT8, 256, 1, 0) == -1   # range needs a whole block
+    assert L.pipesgd_set_launch_config(B.K_ALLGATHER, B.QUANT8, 256, 4, 0) == -1        # 16 KiB > a tile's 4 KiB payload
+    t, q, l = B.get_launch_config(B.K_UPDATE, 0)
+    assert (t * q) in (256, 512, 1024) and l >= 0
