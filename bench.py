@@ -138,7 +138,8 @@ def main() -> int:
     gpu_ms_per_step = start_ev.elapsed_time(stop_ev) / args.steps
     upd_ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
 
-    model = bytes_model(mode, n, p, momentum != 0.0, fused=(schedule == B.FUSED))
+    n_true = int(sum(numels))          # bucket padding is processed but is not part of the model
+    model = bytes_model(mode, n_true, p, momentum != 0.0, fused=(schedule == B.FUSED))
     value = model["total"] / (ms_per_step * 1e-3) / 1e9
     upd_gbs = model["update"] / (upd_ms * 1e-3) / 1e9
 
@@ -158,7 +159,8 @@ def main() -> int:
         "dtype": "f32",
         "data": "synthetic",
         "config": {
-            "workload": f"config{cfg}:{W.CONFIG_NAMES[cfg]}", "workers": p, "elements_per_worker": n,
+            "workload": f"config{cfg}:{W.CONFIG_NAMES[cfg]}", "workers": p, "elements_per_worker": n_true,
+            "packed_elements_per_worker": n,
             "tensors": len(specs), "buckets": len(buckets) if buckets else 1,
             "compression": ["none", "trunc16", "quant8"][mode], "momentum": momentum, "lr": args.lr,
             "pipeline_width": 2, "schedule": args.schedule, "seed": args.seed,

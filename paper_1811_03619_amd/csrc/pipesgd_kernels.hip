@@ -302,15 +302,26 @@ __device__ __forceinline__ void load_f32_full(const float *base, float *x)
 #pragma unroll
     for (int i = 0; i < G::kQuads; ++i) { x[4 * i] = r[i].x; x[4 * i + 1] = r[i].y; x[4 * i + 2] = r[i].z; x[4 * i + 3] = r[i].w; }
 }
+// Short units (1 <= len < kUnit): every lane loads from an index clamped into
+// the unit and the out-of-range values are replaced afterwards, so the loads
+// carry no branches and are all in flight together here too.
 template <class G>
 __device__ __forceinline__ void load_f32_tail(const float *base, uint32_t len, float *x)
 {
+    float r[G::kPerThread];
 #pragma unroll
     for (int i = 0; i < G::kQuads; ++i)
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const uint32_t idx = 4 * (i * G::kThreads + threadIdx.x) + e;
-            x[4 * i + e] = idx < len ? base[idx] : 0.0f;
+            r[4 * i + e] = base[min(idx, len - 1)];
+        }
+#pragma unroll
+    for (int i = 0; i < G::kQuads; ++i)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const uint32_t idx = 4 * (i * G::kThreads + threadIdx.x) + e;
+            x[4 * i + e] = idx < len ? r[4 * i + e] : 0.0f;
         }
 }
 template <class G, bool FULL, bool NT>
@@ -353,12 +364,20 @@ __device__ __forceinline__ void load_payload(const void *pay, uint64_t e0, uint3
 #pragma unroll
         for (int i = 0; i < G::kQuads; ++i) C::decode(r[i], step, x + 4 * i);
     } else {
+        float r[G::kPerThread];
 #pragma unroll
         for (int i = 0; i < G::kQuads; ++i)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const uint32_t idx = 4 * (i * G::kThreads + threadIdx.x) + e;
-                x[4 * i + e] = idx < len ? C::decode1(pay, e0 + idx, step) : 0.0f;
+                r[4 * i + e] = C::decode1(pay, e0 + min(idx, len - 1), step);
+            }
+#pragma unroll
+        for (int i = 0; i < G::kQuads; ++i)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t idx = 4 * (i * G::kThreads + threadIdx.x) + e;
+                x[4 * i + e] = idx < len ? r[4 * i + e] : 0.0f;
             }
     }
 }
