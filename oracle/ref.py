@@ -41,8 +41,12 @@ def build(force: bool = False) -> str:
 def lib():
     global _lib
     if _lib is None:
-        build()
-        L = C.CDLL(_LIB)
+        # PIPESGD_ORACLE_LIB: a deliberately broken build of the oracle, used by
+        # the test that checks that the pins notice planted mistakes.
+        override = os.environ.get("PIPESGD_ORACLE_LIB")
+        if not override:
+            build()
+        L = C.CDLL(override or _LIB)
         vp, sz, i32, u64, f32 = C.c_void_p, C.c_size_t, C.c_int, C.c_uint64, C.c_float
         L.orc_chunk_elems.restype = sz
         L.orc_chunk_elems.argtypes = [sz, i32]
