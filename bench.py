@@ -63,6 +63,8 @@ def main() -> int:
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle timing (0 = skip)")
     ap.add_argument("--phases", action="store_true", help="also time each phase separately")
+    ap.add_argument("--study", choices=["within-allreduce"], default=None,
+                    help="extra measurement printed as its own JSON line after the main one")
     ap.add_argument("--calib-copy", type=int, default=0,
                     help="after the timed region, launch this many plain copies of one worker's gradient "
                          "(pipesgd_compress in mode NONE: reads 4n, writes 4n bytes) so that a rocprofv3 --pmc "
@@ -189,10 +191,16 @@ def main() -> int:
         out["calib_copy"] = {"kernel": "compress_kernel<0>", "launches": args.calib_copy,
                              "read_bytes_per_launch": 4 * n, "write_bytes_per_launch": 4 * n}
 
+    study = None
+    if args.study == "within-allreduce":
+        study = study_within_allreduce(sim, B, torch, np, mode, n, n_true, p)
+
     if args.cpu_seconds > 0:
         out["cpu_baseline"] = cpu_baseline(mode, grads, w0, p, args.lr, momentum, buckets, model["total"],
                                            args.cpu_seconds)
     print(json.dumps(out), flush=True)
+    if study is not None:
+        print(json.dumps(study), flush=True)
     return 0
 
 
@@ -230,6 +238,60 @@ def time_phases(sim, B, torch, np, reps: int = 20):
     res["allreduce_stepwise"] = timed(lambda: B.allreduce_sim(ring, B.STEPWISE))
     res["allreduce_fused"] = timed(lambda: B.allreduce_sim(ring, B.FUSED))
     res["update_all_replicas"] = timed(lambda: sim.update_from(1))
+    return res
+
+
+def study_within_allreduce(sim, B, torch, np, mode, n, n_true, p, reps: int = 15):
+    """Pipelining within the AllReduce (Sec. 3.2, Fig. 3(b)): stage 1 moves each
+    hop's compressed payload into the receiver's staging buffer (the stand-in for
+    the wire) on one stream, stage 2 (decompress, sum, compress) runs on another
+    on what has arrived.  Reports how much of the shorter stage the overlap hides."""
+    if sim.buckets:
+        return {"study": "within-allreduce", "skipped": "single-bucket rings only"}
+    from paper_1811_03619_amd.pipeline import payload_empty
+    dev = sim.device
+    ns = B.num_scales(mode, n)
+    recv = [payload_empty(mode, n, dev) for _ in range(p)]
+    recv_sc = [torch.zeros(max(ns, 1), dtype=torch.float32, device=dev)[:ns] for _ in range(p)] if mode == B.QUANT8 else None
+    ring = sim.rings[0]
+    ov = B.Overlap()
+    wire = torch.cuda.Stream()
+
+    def timed(fn):
+        ts = []
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        for _ in range(reps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(); fn(); b.record()
+            torch.cuda.synchronize()
+            ts.append(a.elapsed_time(b))
+        return float(np.median(ts))
+
+    res = {"study": "within-allreduce", "unit": "ms"}
+    res["in_place_stepwise"] = round(timed(lambda: B.allreduce_sim(ring, B.STEPWISE)), 5)
+    res["reduce_rounds_in_place"] = round(timed(lambda: [B.ring_reduce_scatter_step(ring, s) for s in range(p - 1)]), 5)
+    res["transfer_rounds_only"] = round(timed(lambda: [B.ring_allgather_step(ring, s) for s in range(p - 1)]), 5)
+    res["sequential_transfer_then_reduce"] = round(
+        timed(lambda: B.allreduce_pipelined(ring, recv, recv_sc, 1, ov, None, None)), 5)
+    res["pipelined_full_speed_transfer"] = {}
+    for seg in (1, 2, 4, 8):
+        res["pipelined_full_speed_transfer"][str(seg)] = round(
+            timed(lambda: B.allreduce_pipelined(ring, recv, recv_sc, seg, ov, None, wire)), 5)
+    # a link slower than the reduction: each worker's transfers carried by k workgroups
+    res["limited_link"] = []
+    for k in (64, 32, 16):
+        seq = timed(lambda: B.allreduce_pipelined(ring, recv, recv_sc, 1, ov, None, None, wire_workgroups=k))
+        row = {"wire_workgroups_per_worker": k, "sequential": round(seq, 5), "pipelined": {}}
+        for seg in (2, 4, 8):
+            row["pipelined"][str(seg)] = round(
+                timed(lambda: B.allreduce_pipelined(ring, recv, recv_sc, seg, ov, None, wire, wire_workgroups=k)), 5)
+        best = min(row["pipelined"].values())
+        row["hidden_ms"] = round(seq - best, 5)
+        row["hidden_fraction_of_reduce_stage"] = round((seq - best) / res["reduce_rounds_in_place"], 4)
+        res["limited_link"].append(row)
+    ov.close()
     return res
 
 

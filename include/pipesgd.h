@@ -158,6 +158,38 @@ int pipesgd_ring_allgather_step(const pipesgd_ring *ring, int step, void *stream
  * bytes moved, for launch-bound (small or many-bucket) gradients. */
 int pipesgd_allreduce_sim(const pipesgd_ring *ring, int schedule, void *stream);
 
+/* ---------------------------------------- pipelining within the AllReduce -- */
+
+/* Host-side resources (HIP events) of the two-stream schedule below.  No device
+ * memory.  Not thread-safe; one per concurrently used ring. */
+typedef struct pipesgd_overlap pipesgd_overlap;
+int  pipesgd_overlap_create(pipesgd_overlap **out);
+void pipesgd_overlap_destroy(pipesgd_overlap *ov);
+
+/* The AllReduce as a two-stage pipeline over `segments` sub-blocks of every
+ * ring block (Sec. 3.2, "pipelining within AllReduce", Fig. 3(b)): stage 1,
+ * the compressed communication, copies a sub-block of the sender's payload into
+ * the receiver's staging buffer recv[r] on `wire_stream`; stage 2, (decompress,
+ * sum, compress), runs on `compute_stream` on what has arrived, while the next
+ * sub-block is in transit.  The send-back rounds are communication only.
+ * Same result bits as pipesgd_allreduce_sim.  Unlike the plain schedules, where
+ * a receiver reads the sender's buffer in place, every hop payload here is
+ * moved once more (the stand-in for the wire), so this costs bandwidth on one
+ * GPU; it exists to measure how much of the codec time the transfer hides.
+ * recv / recv_scales: HOST arrays of p DEVICE buffers, each as large as a result
+ * slot (payload of n elements / its scales); contents are scratch.
+ * Only single-bucket rings.  On return both streams hold work; compute_stream
+ * is made to wait for the end of it, and wire_stream for everything enqueued on
+ * compute_stream before the call.  wire_stream may equal compute_stream (no
+ * overlap: the sequential baseline).
+ * wire_workgroups: 0 = every transfer runs at full memory speed.  k > 0 = each
+ * worker's transfers are carried by only k workgroups that walk the sub-block:
+ * a link of limited bandwidth that leaves the rest of the GPU to stage 2, which
+ * is the situation of the paper (the network is slower than the reduction). */
+int pipesgd_allreduce_pipelined(const pipesgd_ring *ring, void *const *recv, float *const *recv_scales,
+                                int segments, int wire_workgroups, pipesgd_overlap *ov,
+                                void *compute_stream, void *wire_stream);
+
 /* ----------------------------------------------------------------- update -- */
 
 /* Algorithm 1, compute thread lines 4-5, on one model replica:

@@ -26,6 +26,7 @@ EXPORTS = [
     "pipesgd_apply_update", "pipesgd_apply_update_multi", "pipesgd_bucket_plan",
     "pipesgd_segments_prepare", "pipesgd_pack", "pipesgd_unpack",
     "pipesgd_set_launch_config", "pipesgd_get_launch_config",
+    "pipesgd_overlap_create", "pipesgd_overlap_destroy", "pipesgd_allreduce_pipelined",
 ]
 K_FIRST_SEND, K_REDUCE_SCATTER, K_ALLGATHER, K_FUSED, K_UPDATE, K_COMPRESS, K_DECOMPRESS = range(7)
 
@@ -110,6 +111,12 @@ def lib():
     L.pipesgd_pack.argtypes = [vp, u64, u64, vp]
     L.pipesgd_unpack.restype = i32
     L.pipesgd_unpack.argtypes = [vp, u64, u64, vp]
+    L.pipesgd_overlap_create.restype = i32
+    L.pipesgd_overlap_create.argtypes = [C.POINTER(vp)]
+    L.pipesgd_overlap_destroy.restype = None
+    L.pipesgd_overlap_destroy.argtypes = [vp]
+    L.pipesgd_allreduce_pipelined.restype = i32
+    L.pipesgd_allreduce_pipelined.argtypes = [C.POINTER(RingStruct), vp, vp, i32, i32, vp, vp, vp]
     L.pipesgd_set_launch_config.restype = i32
     L.pipesgd_set_launch_config.argtypes = [i32, i32, i32, i32, i32]
     L.pipesgd_get_launch_config.restype = i32
@@ -219,6 +226,35 @@ def ring_allgather_step(ring: RingStruct, step: int, stream=None) -> None:
 
 def allreduce_sim(ring: RingStruct, schedule: int = STEPWISE, stream=None) -> None:
     check(lib().pipesgd_allreduce_sim(C.byref(ring), schedule, _stream(stream)), "pipesgd_allreduce_sim")
+
+
+class Overlap:
+    """Owner of a pipesgd_overlap handle (HIP events of the two-stream schedule)."""
+
+    def __init__(self):
+        h = C.c_void_p()
+        check(lib().pipesgd_overlap_create(C.byref(h)), "pipesgd_overlap_create")
+        self.handle = h
+
+    def close(self):
+        if self.handle and _lib is not None:
+            _lib.pipesgd_overlap_destroy(self.handle)
+        self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def allreduce_pipelined(ring: RingStruct, recv: Sequence, recv_scales: Optional[Sequence], segments: int,
+                        overlap: Overlap, compute_stream=None, wire_stream=None, wire_workgroups: int = 0) -> None:
+    check(lib().pipesgd_allreduce_pipelined(C.byref(ring), _ptr_array(recv),
+                                            _ptr_array(recv_scales) if recv_scales is not None else None,
+                                            segments, wire_workgroups, overlap.handle,
+                                            _stream(compute_stream), _stream(wire_stream)),
+          "pipesgd_allreduce_pipelined")
 
 
 def apply_update(mode: int, g_sum_c, scales, n: int, w, v, lr: float, momentum: float = 0.0,

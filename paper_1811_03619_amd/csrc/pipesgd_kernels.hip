@@ -27,10 +27,17 @@
 #include <atomic>
 #include <cfloat>
 #include <cstdint>
+#include <new>
+#include <vector>
 
 #include "pipesgd.h"
 
 #pragma clang fp contract(off)
+
+// Host-side resources of the two-stream schedules: HIP events only.
+struct pipesgd_overlap {
+    std::vector<hipEvent_t> events;
+};
 
 namespace {
 
@@ -97,12 +104,18 @@ struct BucketTable {
     uint64_t n[kMaxB];
 };
 
+// One launch of a ring kernel.  Worker r (blockIdx.y) handles chunk
+// (r - chunk_rot) mod p, tile slots [slot_base, slot_base + gridDim.x / split).
 struct RingArgs {
-    const float *g[kMaxW];
-    void *pay[kMaxW];
-    float *sc[kMaxW];
+    const float *g[kMaxW];      // local gradients
+    const void *in[kMaxW];      // payload worker r receives: the sender's slot, or r's own receive staging
+    const float *in_sc[kMaxW];
+    void *out[kMaxW];           // payload worker r writes
+    float *out_sc[kMaxW];
     int p;
-    int step;
+    int chunk_rot;
+    uint32_t slot_base;
+    uint32_t units;             // copy kernel only: units to cover (gridDim.x may be smaller: a throttled link)
 };
 
 struct UpdateArgs {
@@ -442,22 +455,16 @@ template <int MODE, class G> struct RangeOk {
 // ---------------------------------------------------------------- kernels --
 
 // One ring hop for every worker (blockIdx.y = receiving worker r).
-//   HAS_IN = false: the first send.  C(g_r[chunk r]) -> slot r.
-//   HAS_IN = true : transmit-and-reduce round a.step.  D(slot r-1) + g_r -> C -> slot r.
-//   in_is_grad    : uncompressed round 0 reads the sender's gradient itself.
+//   HAS_IN = false: the first send.  C(g_r[chunk]) -> out_r.
+//   HAS_IN = true : transmit-and-reduce.  D(in_r) + g_r -> C -> out_r.
 template <int MODE, bool HAS_IN, class G, bool FULL>
-__device__ __forceinline__ void ring_hop_body(const RingArgs &a, const UnitRef &t, int r, int in_is_grad, float *red)
+__device__ __forceinline__ void ring_hop_body(const RingArgs &a, const UnitRef &t, int r, float *red)
 {
     float P[G::kPerThread];
     float x[G::kPerThread];
     if (HAS_IN) {
-        const int src = mod_p(r - 1, a.p);
-        if (MODE == PIPESGD_NONE && in_is_grad) {
-            load_f32<G, FULL, kNtGrad>(a.g[src] + t.elem0, t.len, x);
-        } else {
-            const float scale_in = MODE == PIPESGD_QUANT8 ? a.sc[src][t.elem0 / kTile] : 0.0f;
-            load_payload<MODE, G, FULL, kNtPayIn>(a.pay[src], t.elem0, t.len, scale_in, x);
-        }
+        const float scale_in = MODE == PIPESGD_QUANT8 ? a.in_sc[r][t.elem0 / kTile] : 0.0f;
+        load_payload<MODE, G, FULL, kNtPayIn>(a.in[r], t.elem0, t.len, scale_in, x);
     }
     load_f32<G, FULL, kNtGrad>(a.g[r] + t.elem0, t.len, P);
     if (HAS_IN) {
@@ -466,28 +473,29 @@ __device__ __forceinline__ void ring_hop_body(const RingArgs &a, const UnitRef &
     }
     float scale = 0.0f;
     if constexpr (MODE == PIPESGD_QUANT8) scale = tile_absmax<G>(P, red);
-    store_payload<MODE, G, FULL, kNtPayOut>(a.pay[r], a.sc[r], t.elem0, t.len, scale, P);
+    store_payload<MODE, G, FULL, kNtPayOut>(a.out[r], a.out_sc[r], t.elem0, t.len, scale, P);
 }
 
 template <int MODE, bool HAS_IN, class G>
-__global__ __launch_bounds__(G::kThreads) void ring_hop_kernel(RingArgs a, BucketTable bt, int in_is_grad)
+__global__ __launch_bounds__(G::kThreads) void ring_hop_kernel(RingArgs a, BucketTable bt)
 {
     if constexpr (RangeOk<MODE, G>::value) {
         __shared__ float red[G::kWaves];
         const int r = blockIdx.y;
-        const int chunk = HAS_IN ? mod_p(r - a.step - 1, a.p) : r;
-        const UnitRef t = locate<G>(bt, blockIdx.x, chunk);
+        const UnitRef t = locate<G>(bt, blockIdx.x + a.slot_base * G::kSplit, mod_p(r - a.chunk_rot, a.p));
         if (t.empty) return;
-        if (t.full) ring_hop_body<MODE, HAS_IN, G, true>(a, t, r, in_is_grad, red);
-        else        ring_hop_body<MODE, HAS_IN, G, false>(a, t, r, in_is_grad, red);
+        if (t.full) ring_hop_body<MODE, HAS_IN, G, true>(a, t, r, red);
+        else        ring_hop_body<MODE, HAS_IN, G, false>(a, t, r, red);
     }
 }
 
-// One send-back round for every worker: byte copy of a chunk's payload (and
-// scales) from slot r-1 to slot r.  Geometry counts 16-byte vectors here:
-// a workgroup copies THREADS*QUADS of them.
+// Payload transfer for every worker: byte copy of one chunk's payload (and
+// scales) from in_r to out_r.  Used for the send-back rounds (in = the
+// neighbour's slot, out = the worker's own slot) and as the "wire" stage of the
+// pipelined schedule (out = the worker's receive staging).  Geometry counts
+// 16-byte vectors here: a workgroup copies THREADS*QUADS of them.
 template <int MODE, class G>
-__global__ __launch_bounds__(G::kThreads) void ring_allgather_kernel(RingArgs a, BucketTable bt)
+__global__ __launch_bounds__(G::kThreads) void ring_copy_kernel(RingArgs a, BucketTable bt)
 {
     using C = Codec<MODE>;
     constexpr int kTileVecs = kTile * C::kBytes / 16;          // 1024, 512 or 256
@@ -496,26 +504,29 @@ __global__ __launch_bounds__(G::kThreads) void ring_allgather_kernel(RingArgs a,
         constexpr int kSplit = kTileVecs / kUnitVecs;
         constexpr int kUnitElems = kTile / kSplit;
         const int r = blockIdx.y;
-        const int src = mod_p(r - 1, a.p);
-        const int chunk = mod_p(r - a.step, a.p);
-        const UnitRef t = locate<UnitOnly<kUnitElems>>(bt, blockIdx.x, chunk);
-        if (t.empty) return;
-        const char *in = static_cast<const char *>(a.pay[src]) + t.elem0 * C::kBytes;
-        char *out = static_cast<char *>(a.pay[r]) + t.elem0 * C::kBytes;
-        if (t.full) {
-            const u32x4 *vi = reinterpret_cast<const u32x4 *>(in);
-            u32x4 *vo = reinterpret_cast<u32x4 *>(out);
-            u32x4 tmp[G::kQuads];
+        const int chunk = mod_p(r - a.chunk_rot, a.p);
+        // one pass when the grid covers all units; fewer workgroups than units
+        // make each of them walk the range (a link of limited bandwidth)
+        for (uint32_t u = blockIdx.x; u < a.units; u += gridDim.x) {
+            const UnitRef t = locate<UnitOnly<kUnitElems>>(bt, u + a.slot_base * kSplit, chunk);
+            if (t.empty) continue;
+            const char *in = static_cast<const char *>(a.in[r]) + t.elem0 * C::kBytes;
+            char *out = static_cast<char *>(a.out[r]) + t.elem0 * C::kBytes;
+            if (t.full) {
+                const u32x4 *vi = reinterpret_cast<const u32x4 *>(in);
+                u32x4 *vo = reinterpret_cast<u32x4 *>(out);
+                u32x4 tmp[G::kQuads];
 #pragma unroll
-            for (int i = 0; i < G::kQuads; ++i) tmp[i] = ld<kNtPayIn>(vi + i * G::kThreads + threadIdx.x);
+                for (int i = 0; i < G::kQuads; ++i) tmp[i] = ld<kNtPayIn>(vi + i * G::kThreads + threadIdx.x);
 #pragma unroll
-            for (int i = 0; i < G::kQuads; ++i) st<kNtPayOut>(vo + i * G::kThreads + threadIdx.x, tmp[i]);
-        } else {
-            const uint32_t bytes = t.len * C::kBytes;
-            for (uint32_t i = threadIdx.x; i < bytes; i += G::kThreads) out[i] = in[i];
+                for (int i = 0; i < G::kQuads; ++i) st<kNtPayOut>(vo + i * G::kThreads + threadIdx.x, tmp[i]);
+            } else {
+                const uint32_t bytes = t.len * C::kBytes;
+                for (uint32_t i = threadIdx.x; i < bytes; i += G::kThreads) out[i] = in[i];
+            }
+            if (MODE == PIPESGD_QUANT8 && threadIdx.x == 0 && t.elem0 % kTile == 0)
+                a.out_sc[r][t.elem0 / kTile] = a.in_sc[r][t.elem0 / kTile];
         }
-        if (MODE == PIPESGD_QUANT8 && threadIdx.x == 0 && t.elem0 % kTile == 0)
-            a.sc[r][t.elem0 / kTile] = a.sc[src][t.elem0 / kTile];
     }
 }
 
@@ -539,7 +550,7 @@ __device__ __forceinline__ void ring_fused_body(const RingArgs &a, const UnitRef
     }
     float scale = 0.0f;
     if constexpr (MODE == PIPESGD_QUANT8) scale = tile_absmax<G>(P, red[flip]);
-    for (int r = 0; r < p; ++r) store_payload<MODE, G, FULL, true>(a.pay[r], a.sc[r], t.elem0, t.len, scale, P);
+    for (int r = 0; r < p; ++r) store_payload<MODE, G, FULL, true>(a.out[r], a.out_sc[r], t.elem0, t.len, scale, P);
 }
 
 template <int MODE, class G>
@@ -548,7 +559,7 @@ __global__ __launch_bounds__(G::kThreads) void ring_fused_kernel(RingArgs a, Buc
     if constexpr (RangeOk<MODE, G>::value) {
         __shared__ float red[2][G::kWaves];
         const int c = blockIdx.y;
-        const UnitRef t = locate<G>(bt, blockIdx.x, c);
+        const UnitRef t = locate<G>(bt, blockIdx.x + a.slot_base * G::kSplit, c);
         if (t.empty) return;
         if (t.full) ring_fused_body<MODE, G, true>(a, t, c, red);
         else        ring_fused_body<MODE, G, false>(a, t, c, red);
@@ -754,7 +765,7 @@ int prepare_ring(const pipesgd_ring *ring, RingArgs &ra, BucketTable &bt, uint64
     if (ring->num_buckets > 0 && !ring->buckets) return PIPESGD_ERR_ARG;
     const int p = ring->workers;
     for (int r = 0; r < kMaxW; ++r) {
-        ra.g[r] = nullptr; ra.pay[r] = nullptr; ra.sc[r] = nullptr;
+        ra.g[r] = nullptr; ra.in[r] = nullptr; ra.in_sc[r] = nullptr; ra.out[r] = nullptr; ra.out_sc[r] = nullptr;
     }
     for (int r = 0; r < p; ++r) {
         if (ring->n > 0) {
@@ -764,11 +775,19 @@ int prepare_ring(const pipesgd_ring *ring, RingArgs &ra, BucketTable &bt, uint64
         if (!aligned16(ring->g_local[r]) || !aligned16(ring->g_sum_c[r]) || !aligned16(ring->scales[r]))
             return PIPESGD_ERR_ALIGN;
         ra.g[r] = ring->g_local[r];
-        ra.pay[r] = ring->g_sum_c[r];
-        ra.sc[r] = ring->scales[r];
+        ra.out[r] = ring->g_sum_c[r];
+        ra.out_sc[r] = ring->scales[r];
+    }
+    // default wiring: worker r receives what worker r-1 holds in its slot
+    for (int r = 0; r < p; ++r) {
+        const int src = (r + p - 1) % p;
+        ra.in[r] = ring->g_sum_c[src];
+        ra.in_sc[r] = ring->scales[src];
     }
     ra.p = p;
-    ra.step = 0;
+    ra.chunk_rot = 0;
+    ra.slot_base = 0;
+    ra.units = 0;
 
     const pipesgd_bucket whole = {0, ring->n};
     const pipesgd_bucket *b = ring->num_buckets ? ring->buckets : &whole;
@@ -807,14 +826,14 @@ int prepare_ring(const pipesgd_ring *ring, RingArgs &ra, BucketTable &bt, uint64
     }
 
 template <int MODE, bool HAS_IN>
-int launch_hop(const LaunchConfig &c, const RingArgs &ra, const BucketTable &bt, uint64_t slots, int in_is_grad, hipStream_t s)
+int launch_hop(const LaunchConfig &c, const RingArgs &ra, const BucketTable &bt, uint64_t slots, hipStream_t s)
 {
 #define X(T, Q)                                                                                                  \
     if (c.threads == T && c.quads == Q) {                                                                        \
         static std::atomic<uint32_t> done{0};                                                                    \
         using G = Geo<T, Q>;                                                                                     \
         return launch(ring_hop_kernel<MODE, HAS_IN, G>, dim3(static_cast<uint32_t>(slots * G::kSplit), ra.p), T, \
-                      c.lds_bytes, s, done, ra, bt, in_is_grad);                                                 \
+                      c.lds_bytes, s, done, ra, bt);                                                             \
     }
     PIPESGD_FOR_EACH_GEO(X)
 #undef X
@@ -822,7 +841,7 @@ int launch_hop(const LaunchConfig &c, const RingArgs &ra, const BucketTable &bt,
 }
 
 template <int MODE>
-int launch_allgather(const LaunchConfig &c, const RingArgs &ra, const BucketTable &bt, uint64_t slots, hipStream_t s)
+int launch_copy(const LaunchConfig &c, RingArgs ra, const BucketTable &bt, uint64_t slots, uint32_t max_groups, hipStream_t s)
 {
     constexpr int kTileVecs = kTile * Codec<MODE>::kBytes / 16;
 #define X(T, Q)                                                                                                  \
@@ -830,8 +849,9 @@ int launch_allgather(const LaunchConfig &c, const RingArgs &ra, const BucketTabl
         if constexpr (T * Q <= kTileVecs) {                                                                      \
             static std::atomic<uint32_t> done{0};                                                                \
             constexpr int kSplit = kTileVecs / (T * Q);                                                          \
-            return launch(ring_allgather_kernel<MODE, Geo<T, Q>>, dim3(static_cast<uint32_t>(slots * kSplit), ra.p), T, \
-                          c.lds_bytes, s, done, ra, bt);                                                         \
+            ra.units = static_cast<uint32_t>(slots * kSplit);                                                    \
+            const uint32_t gx = (max_groups && max_groups < ra.units) ? max_groups : ra.units;                   \
+            return launch(ring_copy_kernel<MODE, Geo<T, Q>>, dim3(gx, ra.p), T, c.lds_bytes, s, done, ra, bt);   \
         }                                                                                                        \
     }
     PIPESGD_FOR_EACH_GEO(X)
@@ -905,31 +925,41 @@ int launch_update(const LaunchConfig &c, const UpdateArgs &ua, int replicas, hip
     return PIPESGD_ERR_ARG;
 }
 
-int first_send_impl(int mode, const RingArgs &ra, const BucketTable &bt, uint64_t slots, hipStream_t s)
+// The four launches below work on tile slots [ra.slot_base, ra.slot_base + slots)
+// of every bucket-chunk; the plain entry points pass the whole range.
+
+int first_send_impl(int mode, RingArgs ra, const BucketTable &bt, uint64_t slots, hipStream_t s)
 {
     // uncompressed, p > 1: the first round reads the sender's gradient in place
     if (slots == 0 || (mode == PIPESGD_NONE && ra.p > 1)) return PIPESGD_OK;
     const LaunchConfig c = g_cfg[kFirstSend][mode];
-#define CALL(M) return launch_hop<M, false>(c, ra, bt, slots, 0, s);
+    ra.chunk_rot = 0;
+#define CALL(M) return launch_hop<M, false>(c, ra, bt, slots, s);
     PIPESGD_MODE_SWITCH(mode, CALL)
 #undef CALL
     return PIPESGD_ERR_MODE;
 }
 
-int rs_impl(int mode, const RingArgs &ra, const BucketTable &bt, uint64_t slots, hipStream_t s)
+// `staged`: worker r's incoming payload has been put into ra.in[r] by the
+// caller (receive staging); otherwise it is read from the sender's buffers.
+int rs_impl(int mode, RingArgs ra, const BucketTable &bt, uint64_t slots, int step, bool staged, hipStream_t s)
 {
     const LaunchConfig c = g_cfg[kReduceScatter][mode];
-    const int in_is_grad = (mode == PIPESGD_NONE && ra.step == 0) ? 1 : 0;
-#define CALL(M) return launch_hop<M, true>(c, ra, bt, slots, in_is_grad, s);
+    ra.chunk_rot = step + 1;
+    if (!staged && mode == PIPESGD_NONE && step == 0)
+        for (int r = 0; r < ra.p; ++r) ra.in[r] = ra.g[(r + ra.p - 1) % ra.p];
+#define CALL(M) return launch_hop<M, true>(c, ra, bt, slots, s);
     PIPESGD_MODE_SWITCH(mode, CALL)
 #undef CALL
     return PIPESGD_ERR_MODE;
 }
 
-int ag_impl(int mode, const RingArgs &ra, const BucketTable &bt, uint64_t slots, hipStream_t s)
+// Copy chunk (r - rot) mod p from ra.in[r] to ra.out[r] for every worker.
+int copy_impl(int mode, RingArgs ra, const BucketTable &bt, uint64_t slots, int rot, uint32_t max_groups, hipStream_t s)
 {
     const LaunchConfig c = g_cfg[kAllGather][mode];
-#define CALL(M) return launch_allgather<M>(c, ra, bt, slots, s);
+    ra.chunk_rot = rot;
+#define CALL(M) return launch_copy<M>(c, ra, bt, slots, max_groups, s);
     PIPESGD_MODE_SWITCH(mode, CALL)
 #undef CALL
     return PIPESGD_ERR_MODE;
@@ -1013,8 +1043,7 @@ int pipesgd_ring_reduce_scatter_step(const pipesgd_ring *ring, int step, void *s
     if (rc != PIPESGD_OK) return rc;
     if (step < 0 || step > ring->workers - 2) return PIPESGD_ERR_ARG;
     if (slots == 0) return PIPESGD_OK;
-    ra.step = step;
-    return rs_impl(ring->mode, ra, bt, slots, static_cast<hipStream_t>(stream));
+    return rs_impl(ring->mode, ra, bt, slots, step, false, static_cast<hipStream_t>(stream));
 }
 
 int pipesgd_ring_allgather_step(const pipesgd_ring *ring, int step, void *stream)
@@ -1024,8 +1053,7 @@ int pipesgd_ring_allgather_step(const pipesgd_ring *ring, int step, void *stream
     if (rc != PIPESGD_OK) return rc;
     if (step < 0 || step > ring->workers - 2) return PIPESGD_ERR_ARG;
     if (slots == 0) return PIPESGD_OK;
-    ra.step = step;
-    return ag_impl(ring->mode, ra, bt, slots, static_cast<hipStream_t>(stream));
+    return copy_impl(ring->mode, ra, bt, slots, step, 0, static_cast<hipStream_t>(stream));
 }
 
 int pipesgd_allreduce_sim(const pipesgd_ring *ring, int schedule, void *stream)
@@ -1039,15 +1067,124 @@ int pipesgd_allreduce_sim(const pipesgd_ring *ring, int schedule, void *stream)
     const int mode = ring->mode, p = ring->workers;
     if (schedule == PIPESGD_FUSED) return fused_impl(mode, ra, bt, slots, s);
     rc = first_send_impl(mode, ra, bt, slots, s);
-    for (int step = 0; rc == PIPESGD_OK && step <= p - 2; ++step) {
-        ra.step = step;
-        rc = rs_impl(mode, ra, bt, slots, s);
-    }
-    for (int step = 0; rc == PIPESGD_OK && step <= p - 2; ++step) {
-        ra.step = step;
-        rc = ag_impl(mode, ra, bt, slots, s);
-    }
+    for (int step = 0; rc == PIPESGD_OK && step <= p - 2; ++step) rc = rs_impl(mode, ra, bt, slots, step, false, s);
+    for (int step = 0; rc == PIPESGD_OK && step <= p - 2; ++step) rc = copy_impl(mode, ra, bt, slots, step, 0, s);
     return rc;
+}
+
+
+// ------------------------------------------ pipelining within the AllReduce --
+
+int pipesgd_overlap_create(pipesgd_overlap **out)
+{
+    if (!out) return PIPESGD_ERR_ARG;
+    pipesgd_overlap *ov = new (std::nothrow) pipesgd_overlap();
+    if (!ov) return PIPESGD_ERR_CAPACITY;
+    *out = ov;
+    return PIPESGD_OK;
+}
+
+void pipesgd_overlap_destroy(pipesgd_overlap *ov)
+{
+    if (!ov) return;
+    for (hipEvent_t e : ov->events) (void)hipEventDestroy(e);
+    delete ov;
+}
+
+static bool overlap_event(pipesgd_overlap *ov, size_t i, hipEvent_t *e)
+{
+    while (ov->events.size() <= i) {
+        hipEvent_t ne;
+        if (hipEventCreateWithFlags(&ne, hipEventDisableTiming) != hipSuccess) return false;
+        ov->events.push_back(ne);
+    }
+    *e = ov->events[i];
+    return true;
+}
+
+int pipesgd_allreduce_pipelined(const pipesgd_ring *ring, void *const *recv, float *const *recv_scales,
+                                int segments, int wire_workgroups, pipesgd_overlap *ov,
+                                void *compute_stream, void *wire_stream)
+{
+    RingArgs ra; BucketTable bt; uint64_t slots = 0;
+    int rc = prepare_ring(ring, ra, bt, slots);
+    if (rc != PIPESGD_OK) return rc;
+    if (!ov || segments < 1 || wire_workgroups < 0 || ring->num_buckets > 1) return PIPESGD_ERR_ARG;
+    const int mode = ring->mode, p = ring->workers;
+    if (slots == 0) return PIPESGD_OK;
+    if (p > 1) {
+        if (!recv || (mode == PIPESGD_QUANT8 && !recv_scales)) return PIPESGD_ERR_ARG;
+        for (int r = 0; r < p; ++r) {
+            if (!recv[r] || (mode == PIPESGD_QUANT8 && !recv_scales[r])) return PIPESGD_ERR_ARG;
+            if (!aligned16(recv[r]) || (mode == PIPESGD_QUANT8 && !aligned16(recv_scales[r]))) return PIPESGD_ERR_ALIGN;
+        }
+    }
+    hipStream_t cs = static_cast<hipStream_t>(compute_stream), ws = static_cast<hipStream_t>(wire_stream);
+    const uint64_t S = static_cast<uint64_t>(segments) < slots ? static_cast<uint64_t>(segments) : slots;
+    auto seg_lo = [&](uint64_t g) { return slots * g / S; };
+
+    // event layout: [0] entry, [1] done, then per segment: sent, and per (round, segment): copied, reduced
+    size_t next_event = 0;
+    auto record = [&](hipStream_t st, hipEvent_t *out_e) -> bool {
+        hipEvent_t e;
+        if (!overlap_event(ov, next_event++, &e)) return false;
+        if (hipEventRecord(e, st) != hipSuccess) return false;
+        *out_e = e;
+        return true;
+    };
+    auto wait = [&](hipStream_t st, hipEvent_t e) -> bool { return hipStreamWaitEvent(st, e, 0) == hipSuccess; };
+
+    hipEvent_t entry;
+    if (!record(cs, &entry) || !wait(ws, entry)) return PIPESGD_ERR_HIP;
+
+    std::vector<hipEvent_t> ready(S, entry);          // per segment: what the next wire copy must wait for
+    for (uint64_t g = 0; g < S; ++g) {                // first send, segment by segment
+        RingArgs a = ra;
+        a.slot_base = static_cast<uint32_t>(seg_lo(g));
+        rc = first_send_impl(mode, a, bt, seg_lo(g + 1) - seg_lo(g), cs);
+        if (rc != PIPESGD_OK) return rc;
+        if (!(mode == PIPESGD_NONE && p > 1) && !record(cs, &ready[g])) return PIPESGD_ERR_HIP;
+    }
+    for (int step = 0; step <= p - 2; ++step) {
+        for (uint64_t g = 0; g < S; ++g) {
+            const uint64_t count = seg_lo(g + 1) - seg_lo(g);
+            // stage 1, "compressed communication": the sender's payload travels into the receiver's staging
+            RingArgs w = ra;
+            w.slot_base = static_cast<uint32_t>(seg_lo(g));
+            for (int r = 0; r < p; ++r) {
+                const int src = (r + p - 1) % p;
+                w.in[r] = (mode == PIPESGD_NONE && step == 0) ? static_cast<const void *>(ra.g[src]) : ra.out[src];
+                w.in_sc[r] = ra.out_sc[src];
+                w.out[r] = recv[r];
+                w.out_sc[r] = mode == PIPESGD_QUANT8 ? recv_scales[r] : nullptr;
+            }
+            if (!wait(ws, ready[g])) return PIPESGD_ERR_HIP;
+            rc = copy_impl(mode, w, bt, count, step + 1, static_cast<uint32_t>(wire_workgroups), ws);
+            if (rc != PIPESGD_OK) return rc;
+            hipEvent_t copied;
+            if (!record(ws, &copied) || !wait(cs, copied)) return PIPESGD_ERR_HIP;
+            // stage 2, (decompress, sum, compress) on what has arrived
+            RingArgs h = ra;
+            h.slot_base = static_cast<uint32_t>(seg_lo(g));
+            for (int r = 0; r < p; ++r) {
+                h.in[r] = recv[r];
+                h.in_sc[r] = mode == PIPESGD_QUANT8 ? recv_scales[r] : nullptr;
+            }
+            rc = rs_impl(mode, h, bt, count, step, true, cs);
+            if (rc != PIPESGD_OK) return rc;
+            if (!record(cs, &ready[g])) return PIPESGD_ERR_HIP;
+        }
+    }
+    // send-back rounds: communication only, on the wire stream, after the last reductions
+    hipEvent_t reduced_all;
+    if (!record(cs, &reduced_all) || !wait(ws, reduced_all)) return PIPESGD_ERR_HIP;
+    for (int step = 0; step <= p - 2; ++step) {
+        rc = copy_impl(mode, ra, bt, slots, step, static_cast<uint32_t>(wire_workgroups), ws);
+        if (rc != PIPESGD_OK) return rc;
+    }
+    hipEvent_t done;
+    if (!record(ws, &done) || !wait(cs, done)) return PIPESGD_ERR_HIP;
+    return PIPESGD_OK;
 }
 
 int pipesgd_apply_update_multi(int mode, int replicas, const void *const *g_sum_c,

@@ -485,3 +485,52 @@ def test_launch_config_validation():
     assert L.pipesgd_set_launch_config(B.K_ALLGATHER, B.QUANT8, 256, 4, 0) == -1        # 16 KiB > a tile's 4 KiB payload
     t, q, l = B.get_launch_config(B.K_UPDATE, 0)
     assert (t * q) in (256, 512, 1024) and l >= 0
+
+
+# -------------------------------------- pipelining within the AllReduce --
+
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("p,n,segments", [(4, 4096 * 37 + 555, 4), (4, 4096 * 37 + 555, 1), (3, 50001, 3),
+                                          (2, 4096 * 8, 64), (1, 9000, 2), (5, 12289, 2), (8, 300007, 5)])
+@pytest.mark.parametrize("two_streams", [True, False])
+def test_allreduce_pipelined_equals_oracle(orc, mode, p, n, segments, two_streams):
+    grads = [special_values(n, 17 * p + r) for r in range(p)]
+    want = orc.allreduce(mode, grads)
+    g_dev, slots, scs = ring_buffers(mode, grads)
+    recv = [pay_buf(mode, n) for _ in range(p)]
+    recv_sc = [dev_zeros(B.num_scales(mode, n), fill=-2.0) for _ in range(p)]
+    ring = B.make_ring(mode, n, g_dev, slots, scs if mode == B.QUANT8 else None)
+    ov = B.Overlap()
+    wire = torch.cuda.Stream() if two_streams else None
+    for rep in range(2):                       # the second call reuses the events
+        if rep == 1:
+            for t in slots:
+                t.fill_(0x33 if mode != B.NONE else 7.0)
+        B.allreduce_pipelined(ring, recv, recv_sc if mode == B.QUANT8 else None, segments, ov,
+                              None, wire if two_streams else None, wire_workgroups=(0 if rep == 0 else 3))
+        sync()
+        for r in range(p):
+            if mode == B.NONE:
+                assert_fp32_close_then_exact(down(slots[r]), want[r][0], f"sum r={r} rep={rep}")
+            else:
+                assert_bits_equal(down(slots[r], mode), want[r][0], f"payload r={r} rep={rep}")
+            if mode == B.QUANT8:
+                assert_bits_equal(down(scs[r]), want[r][1], f"scales r={r} rep={rep}")
+    ov.close()
+
+
+def test_allreduce_pipelined_rejects_buckets_and_bad_arguments():
+    n = 4096 * 4
+    g = [dev_zeros(n) for _ in range(2)]
+    slots = [pay_buf(B.TRUNC16, n) for _ in range(2)]
+    recv = [pay_buf(B.TRUNC16, n) for _ in range(2)]
+    ov = B.Overlap()
+    ring = B.make_ring(B.TRUNC16, n, g, slots, None, [(0, 8192), (8192, 8192)])
+    with pytest.raises(B.PipeSgdError):
+        B.allreduce_pipelined(ring, recv, None, 2, ov)
+    ring = B.make_ring(B.TRUNC16, n, g, slots, None)
+    with pytest.raises(B.PipeSgdError):
+        B.allreduce_pipelined(ring, recv, None, 0, ov)
+    with pytest.raises(B.PipeSgdError):
+        B.allreduce_pipelined(ring, [recv[0], None], None, 2, ov)
+    sync()
