@@ -63,7 +63,7 @@ def main() -> int:
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle timing (0 = skip)")
     ap.add_argument("--phases", action="store_true", help="also time each phase separately")
-    ap.add_argument("--study", choices=["within-allreduce"], default=None,
+    ap.add_argument("--study", choices=["within-allreduce", "two-thread-runtime"], default=None,
                     help="extra measurement printed as its own JSON line after the main one")
     ap.add_argument("--calib-copy", type=int, default=0,
                     help="after the timed region, launch this many plain copies of one worker's gradient "
@@ -195,6 +195,9 @@ def main() -> int:
     if args.study == "within-allreduce":
         study = study_within_allreduce(sim, B, torch, np, mode, n, n_true, p)
 
+    if args.study == "two-thread-runtime":
+        study = study_two_thread_runtime(sim, B, torch, np, schedule)
+
     if args.cpu_seconds > 0:
         out["cpu_baseline"] = cpu_baseline(mode, grads, w0, p, args.lr, momentum, buckets, model["total"],
                                            args.cpu_seconds)
@@ -293,6 +296,63 @@ def study_within_allreduce(sim, B, torch, np, mode, n, n_true, p, reps: int = 15
         res["limited_link"].append(row)
     ov.close()
     return res
+
+
+def study_two_thread_runtime(sim, B, torch, np, schedule, iters: int = 30):
+    """Algorithm 1's two threads as two streams: time per iteration against the
+    duration of the compute stand-in, for width 2 (pipelined) and width 1
+    (synchronous), next to Eq. 4 and Eq. 2 evaluated on the separately measured
+    l_up and l_comm."""
+    import time as _time
+    rt = B.Runtime()
+    p = sim.p
+
+    def alone(fn, reps=20):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        t0 = _time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (_time.perf_counter() - t0) / reps * 1e3
+
+    l_up = alone(lambda: sim.update_from(1))
+    l_comm = alone(lambda: B.allreduce_sim(sim.rings[0], schedule))
+
+    def per_iter(width, compute_us, wire_us):
+        def run(k):
+            for i in range(k):
+                cur = i % 2
+                rt.iteration(sim.rings[cur], sim.updates[1 - cur], sim.updates[cur], schedule, width,
+                             sim.lr, sim.momentum, sim.grad_scale, compute_us=compute_us, compute_workgroups=16,
+                             wire_us=wire_us)
+        run(4)
+        rt.sync()
+        t0 = _time.perf_counter()
+        run(iters)
+        rt.sync()
+        return (_time.perf_counter() - t0) / iters * 1e3
+
+    tables = []
+    for wire in (0.0, 1.0):                   # ms the payloads spend "on the network"
+        rows = []
+        for l_comp in (0.0, 0.2, 0.4, 0.6, 0.8, 1.0, 1.4, 1.8):
+            w2, w1 = per_iter(2, l_comp * 1e3, wire * 1e3), per_iter(1, l_comp * 1e3, wire * 1e3)
+            lc = l_comm + wire
+            rows.append({"l_comp": l_comp, "pipelined": round(w2, 4), "synchronous": round(w1, 4),
+                         "eq4": round(B.model_pipe_time(1, l_up, l_comp, lc), 4),
+                         "eq4_one_gpu": round(max(l_up + l_comm + l_comp, lc), 4),
+                         "eq2": round(B.model_sync_time(1, l_up, l_comp, lc), 4),
+                         "eq7_scaling_efficiency": round(B.model_scaling_efficiency(l_up, l_comp, lc), 4)})
+        tables.append({"wire_ms": wire, "l_comm": round(l_comm + wire, 4), "rows": rows})
+    rt.close()
+    return {"study": "two-thread-runtime", "unit": "ms", "l_up": round(l_up, 4), "l_comm": round(l_comm, 4),
+            "note": "eq4 = max(l_up + l_comp, l_comm) assumes the two threads use separate resources.  On one GPU the "
+                    "AllReduce kernels and the update share HBM bandwidth, so the kernels' time lands on the compute "
+                    "side as well: eq4_one_gpu = max(l_up + l_allreduce_kernels + l_comp, l_allreduce_kernels + wire); "
+                    "the wire delay and the compute stand-in use no bandwidth",
+            "tables": tables}
 
 
 def cpu_baseline(mode, grads, w0, p, lr, momentum, buckets, bytes_total, budget_s):

@@ -245,6 +245,77 @@ int pipesgd_segments_prepare(pipesgd_segment *segments, uint64_t num, uint64_t *
 int pipesgd_pack(const pipesgd_segment *segments, uint64_t num, uint64_t total_tiles, void *stream);
 int pipesgd_unpack(const pipesgd_segment *segments, uint64_t num, uint64_t total_tiles, void *stream);
 
+/* ------------------------------------------------- Algorithm 1's two threads -- */
+
+/* The per-worker runtime of Algorithm 1 for the p simulated workers at once:
+ * the computation thread and the communication thread are two HIP streams of
+ * default priority that the runtime owns, the "ready" marks are HIP events.
+ * Indexing as elsewhere in this library: g[t] is the gradient evaluated at
+ * w[t-1], A[t] = AllReduce(g[t]), w[t] = Update(w[t-1], A[t-1]) (Algorithm 1
+ * counts the same steps one iteration later).  Iteration t enqueues
+ *   comm stream:    wait "g[t] ready"; AllReduce (comm thread line 4); mark A[t] ready;
+ *   compute stream: wait "A[t-1] ready"; decompress + update all replicas -> w[t]
+ *                   (compute thread lines 3-5); the stand-in for batch / forward /
+ *                   backward that yields g[t+1] (lines 6-8); mark it ready (line 10).
+ * So the AllReduce of g[t] overlaps the update and the gradient computation that
+ * follow it, and the time per iteration follows max(l_up + l_comp, l_comm)
+ * (Eq. 4) as far as the two streams do not compete for the same resource.
+ * width 1 is decentralised synchronous SGD: compute g[t], AllReduce, update with
+ * A[t], one after the other (Eq. 2: l_up + l_comp + l_comm).
+ * The caller keeps the two slot sets and alternates them: `ring` writes the
+ * slot set of iteration t, `stale_*` name the slot set of iteration t-1 (an
+ * all-zero set at t = 1), `fresh_*` the set `ring` writes (width 1 only).
+ * The caller must not change g_local while an AllReduce that reads it may still
+ * be running (pipesgd_runtime_sync, or double-buffer the gradients). */
+typedef struct pipesgd_runtime pipesgd_runtime;
+
+typedef struct pipesgd_runtime_iter {
+    const pipesgd_ring *ring;            /* AllReduce of this iteration (HOST struct) */
+    int32_t  schedule;                   /* PIPESGD_STEPWISE / PIPESGD_FUSED */
+    int32_t  width;                      /* 2 = pipelined (staleness 1), 1 = synchronous */
+    int32_t  replicas;                   /* model replicas to update (normally ring->workers) */
+    int32_t  compute_workgroups;         /* workgroups the compute stand-in occupies (>= 1) */
+    float    compute_us;                 /* duration of the compute stand-in, microseconds (0 = none) */
+    float    wire_us;                    /* extra delay on the comm stream after the AllReduce kernels: the time
+                                            the payloads would spend on a network (Eq. 5's alpha and beta terms);
+                                            it occupies one wavefront and no memory bandwidth (0 = none) */
+    float    lr, momentum, grad_scale;
+    int32_t  reserved;                   /* must be 0 */
+    const void  *const *stale_g_sum_c;   /* HOST arrays of DEVICE pointers, as for pipesgd_apply_update_multi */
+    const float *const *stale_scales;
+    const void  *const *fresh_g_sum_c;   /* width 1 only */
+    const float *const *fresh_scales;
+    float *const *w;
+    float *const *v;
+} pipesgd_runtime_iter;
+
+int   pipesgd_runtime_create(pipesgd_runtime **out);
+void  pipesgd_runtime_destroy(pipesgd_runtime *rt);       /* synchronises both streams first */
+int   pipesgd_runtime_iteration(pipesgd_runtime *rt, const pipesgd_runtime_iter *it);
+int   pipesgd_runtime_sync(pipesgd_runtime *rt);          /* host waits for both streams */
+void *pipesgd_runtime_stream(pipesgd_runtime *rt, int which);   /* 0 = compute, 1 = comm: a hipStream_t */
+
+/* The stand-in for forward + backward: `workgroups` workgroups of 64 threads
+ * that do nothing for duration_us microseconds (0..1e6) and touch no memory. */
+int pipesgd_synthetic_compute(float duration_us, int workgroups, void *stream);
+
+/* ------------------------------------------------------------ timing models -- */
+
+/* The paper's wall-clock models, HOST arithmetic only; times in any one unit.
+ *   Eq. 2  synchronous:        T (l_up + l_comp + l_comm)
+ *   Eq. 3  ideal pipeline:     T/K (l_up + l_comp + l_comm)
+ *   Eq. 4  resource bound:     T max(l_up + l_comp, l_comm)     (any K >= 2)
+ *   Eq. 5/6 ring AllReduce:    2(p-1) L alpha + 2((p-1)/p) n beta + ((p-1)/p) n gamma + L S
+ *           (alpha latency per round, beta transfer time per byte, gamma reduction
+ *            time per byte, S synchronisation, L gradient segments; L = 1 is Eq. 5)
+ *   Eq. 7  scaling efficiency: (l_up + l_comp) / max(l_up + l_comp, l_comm)          */
+double pipesgd_model_sync_time(double T, double l_up, double l_comp, double l_comm);
+double pipesgd_model_pipe_ideal_time(double T, double K, double l_up, double l_comp, double l_comm);
+double pipesgd_model_pipe_time(double T, double l_up, double l_comp, double l_comm);
+double pipesgd_model_ring_comm_time(int p, double n_bytes, double alpha, double beta, double gamma,
+                                    double S, int L);
+double pipesgd_model_scaling_efficiency(double l_up, double l_comp, double l_comm);
+
 /* ----------------------------------------------------------------- tuning -- */
 
 /* Launch geometry of one kernel family for one compression mode.  Optional:

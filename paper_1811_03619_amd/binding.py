@@ -27,6 +27,10 @@ EXPORTS = [
     "pipesgd_segments_prepare", "pipesgd_pack", "pipesgd_unpack",
     "pipesgd_set_launch_config", "pipesgd_get_launch_config",
     "pipesgd_overlap_create", "pipesgd_overlap_destroy", "pipesgd_allreduce_pipelined",
+    "pipesgd_runtime_create", "pipesgd_runtime_destroy", "pipesgd_runtime_iteration", "pipesgd_runtime_sync",
+    "pipesgd_runtime_stream", "pipesgd_synthetic_compute",
+    "pipesgd_model_sync_time", "pipesgd_model_pipe_ideal_time", "pipesgd_model_pipe_time",
+    "pipesgd_model_ring_comm_time", "pipesgd_model_scaling_efficiency",
 ]
 K_FIRST_SEND, K_REDUCE_SCATTER, K_ALLGATHER, K_FUSED, K_UPDATE, K_COMPRESS, K_DECOMPRESS = range(7)
 
@@ -50,6 +54,18 @@ class RingStruct(C.Structure):
         ("g_local", C.c_void_p * MAX_WORKERS),
         ("g_sum_c", C.c_void_p * MAX_WORKERS),
         ("scales", C.c_void_p * MAX_WORKERS),
+    ]
+
+
+class RuntimeIter(C.Structure):
+    _fields_ = [
+        ("ring", C.POINTER(RingStruct)),
+        ("schedule", C.c_int32), ("width", C.c_int32), ("replicas", C.c_int32), ("compute_workgroups", C.c_int32),
+        ("compute_us", C.c_float), ("wire_us", C.c_float), ("lr", C.c_float), ("momentum", C.c_float),
+        ("grad_scale", C.c_float), ("reserved", C.c_int32),
+        ("stale_g_sum_c", C.c_void_p), ("stale_scales", C.c_void_p),
+        ("fresh_g_sum_c", C.c_void_p), ("fresh_scales", C.c_void_p),
+        ("w", C.c_void_p), ("v", C.c_void_p),
     ]
 
 
@@ -117,6 +133,25 @@ def lib():
     L.pipesgd_overlap_destroy.argtypes = [vp]
     L.pipesgd_allreduce_pipelined.restype = i32
     L.pipesgd_allreduce_pipelined.argtypes = [C.POINTER(RingStruct), vp, vp, i32, i32, vp, vp, vp]
+    L.pipesgd_runtime_create.restype = i32
+    L.pipesgd_runtime_create.argtypes = [C.POINTER(vp)]
+    L.pipesgd_runtime_destroy.restype = None
+    L.pipesgd_runtime_destroy.argtypes = [vp]
+    L.pipesgd_runtime_iteration.restype = i32
+    L.pipesgd_runtime_iteration.argtypes = [vp, C.POINTER(RuntimeIter)]
+    L.pipesgd_runtime_sync.restype = i32
+    L.pipesgd_runtime_sync.argtypes = [vp]
+    L.pipesgd_runtime_stream.restype = vp
+    L.pipesgd_runtime_stream.argtypes = [vp, i32]
+    L.pipesgd_synthetic_compute.restype = i32
+    L.pipesgd_synthetic_compute.argtypes = [f32, i32, vp]
+    dbl = C.c_double
+    for name, nargs in (("pipesgd_model_sync_time", 4), ("pipesgd_model_pipe_ideal_time", 5),
+                        ("pipesgd_model_pipe_time", 4), ("pipesgd_model_scaling_efficiency", 3)):
+        getattr(L, name).restype = dbl
+        getattr(L, name).argtypes = [dbl] * nargs
+    L.pipesgd_model_ring_comm_time.restype = dbl
+    L.pipesgd_model_ring_comm_time.argtypes = [i32, dbl, dbl, dbl, dbl, dbl, i32]
     L.pipesgd_set_launch_config.restype = i32
     L.pipesgd_set_launch_config.argtypes = [i32, i32, i32, i32, i32]
     L.pipesgd_get_launch_config.restype = i32
@@ -257,6 +292,52 @@ def allreduce_pipelined(ring: RingStruct, recv: Sequence, recv_scales: Optional[
           "pipesgd_allreduce_pipelined")
 
 
+class Runtime:
+    """Owner of a pipesgd_runtime handle (Algorithm 1's two threads as two streams)."""
+
+    def __init__(self):
+        h = C.c_void_p()
+        check(lib().pipesgd_runtime_create(C.byref(h)), "pipesgd_runtime_create")
+        self.handle = h
+
+    def iteration(self, ring: RingStruct, stale: "UpdateArgs", fresh: Optional["UpdateArgs"], schedule: int,
+                  width: int, lr: float, momentum: float, grad_scale: float = 1.0, compute_us: float = 0.0,
+                  compute_workgroups: int = 1, wire_us: float = 0.0) -> None:
+        it = RuntimeIter()
+        it.ring = C.pointer(ring)
+        it.schedule, it.width, it.replicas, it.compute_workgroups = schedule, width, stale.replicas, compute_workgroups
+        it.compute_us, it.wire_us, it.lr, it.momentum, it.grad_scale, it.reserved = compute_us, wire_us, lr, momentum, grad_scale, 0
+        it.stale_g_sum_c = C.cast(stale.g_sum_c, C.c_void_p)
+        it.stale_scales = C.cast(stale.scales, C.c_void_p) if stale.scales is not None else None
+        if fresh is not None:
+            it.fresh_g_sum_c = C.cast(fresh.g_sum_c, C.c_void_p)
+            it.fresh_scales = C.cast(fresh.scales, C.c_void_p) if fresh.scales is not None else None
+        it.w = C.cast(stale.w, C.c_void_p)
+        it.v = C.cast(stale.v, C.c_void_p) if stale.v is not None else None
+        check(lib().pipesgd_runtime_iteration(self.handle, C.byref(it)), "pipesgd_runtime_iteration")
+
+    def sync(self) -> None:
+        check(lib().pipesgd_runtime_sync(self.handle), "pipesgd_runtime_sync")
+
+    def stream(self, which: int) -> int:
+        return lib().pipesgd_runtime_stream(self.handle, which)
+
+    def close(self):
+        if self.handle and _lib is not None:
+            _lib.pipesgd_runtime_destroy(self.handle)
+        self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def synthetic_compute(duration_us: float, workgroups: int = 1, stream=None) -> None:
+    check(lib().pipesgd_synthetic_compute(duration_us, workgroups, _stream(stream)), "pipesgd_synthetic_compute")
+
+
 def apply_update(mode: int, g_sum_c, scales, n: int, w, v, lr: float, momentum: float = 0.0,
                  grad_scale: float = 1.0, stream=None) -> None:
     check(lib().pipesgd_apply_update(mode, _ptr(g_sum_c), _ptr(scales), n, _ptr(w), _ptr(v),
@@ -291,6 +372,26 @@ def get_launch_config(kernel: int, mode: int) -> Tuple[int, int, int]:
     check(lib().pipesgd_get_launch_config(kernel, mode, C.byref(t), C.byref(q), C.byref(l)),
           "pipesgd_get_launch_config")
     return t.value, q.value, l.value
+
+
+def model_sync_time(T, l_up, l_comp, l_comm):
+    return lib().pipesgd_model_sync_time(T, l_up, l_comp, l_comm)
+
+
+def model_pipe_ideal_time(T, K, l_up, l_comp, l_comm):
+    return lib().pipesgd_model_pipe_ideal_time(T, K, l_up, l_comp, l_comm)
+
+
+def model_pipe_time(T, l_up, l_comp, l_comm):
+    return lib().pipesgd_model_pipe_time(T, l_up, l_comp, l_comm)
+
+
+def model_ring_comm_time(p, n_bytes, alpha, beta, gamma, S=0.0, L=1):
+    return lib().pipesgd_model_ring_comm_time(p, n_bytes, alpha, beta, gamma, S, L)
+
+
+def model_scaling_efficiency(l_up, l_comp, l_comm):
+    return lib().pipesgd_model_scaling_efficiency(l_up, l_comp, l_comm)
 
 
 def bucket_plan(numels: Sequence[int], bucket_elems: int = 1 << 20, max_buckets: int = MAX_BUCKETS):

@@ -14,7 +14,7 @@ CSRC = os.path.join(_HERE, "csrc")
 INCLUDE = os.path.join(ROOT, "include")
 LIB_PATH = os.path.join(_HERE, "libpipesgd.so")
 
-SOURCES = ["pipesgd_kernels.hip", "pipesgd_host.cpp"]
+SOURCES = ["pipesgd_kernels.hip", "pipesgd_runtime.hip", "pipesgd_host.cpp"]
 
 # One IEEE rounding per written operation: no contraction, no fast-math.
 # Packed-fp32 instruction selection is switched off on purpose.

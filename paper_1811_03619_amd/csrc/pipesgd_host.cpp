@@ -93,4 +93,38 @@ int pipesgd_segments_prepare(pipesgd_segment *segments, uint64_t num, uint64_t *
     return PIPESGD_OK;
 }
 
+// ---- the paper's timing models (Sec. 3.1 and 3.2): plain arithmetic ----
+
+double pipesgd_model_sync_time(double T, double l_up, double l_comp, double l_comm)
+{
+    return T * (l_up + l_comp + l_comm);                                  // Eq. 2
+}
+
+double pipesgd_model_pipe_ideal_time(double T, double K, double l_up, double l_comp, double l_comm)
+{
+    return K > 0 ? T / K * (l_up + l_comp + l_comm) : 0.0;                // Eq. 3
+}
+
+double pipesgd_model_pipe_time(double T, double l_up, double l_comp, double l_comm)
+{
+    const double a = l_up + l_comp;
+    return T * (a > l_comm ? a : l_comm);                                 // Eq. 4
+}
+
+double pipesgd_model_ring_comm_time(int p, double n_bytes, double alpha, double beta, double gamma,
+                                    double S, int L)
+{
+    if (p < 1 || L < 1) return 0.0;
+    const double f = static_cast<double>(p - 1) / p;
+    // communication term of Eq. 5 (L = 1) / Eq. 6 (L segments)
+    return 2.0 * (p - 1) * L * alpha + 2.0 * f * n_bytes * beta + f * n_bytes * gamma + L * S;
+}
+
+double pipesgd_model_scaling_efficiency(double l_up, double l_comp, double l_comm)
+{
+    const double a = l_up + l_comp;
+    const double m = a > l_comm ? a : l_comm;
+    return m > 0 ? a / m : 0.0;                                           // Eq. 7
+}
+
 }  // extern "C"

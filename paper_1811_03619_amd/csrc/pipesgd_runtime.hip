@@ -1,0 +1,150 @@
+// The per-worker runtime of Algorithm 1 (arXiv 1811.03619) on one GPU: the
+// paper's compute thread and communication thread become two HIP streams, its
+// "ready" flags become HIP events.  Built on the library's public entry points
+// only; the one kernel here is the stand-in for forward + backward.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <new>
+
+#include "pipesgd.h"
+
+namespace {
+
+// Stand-in for "load a batch, forward pass, backward pass" (Alg. 1, compute
+// thread lines 6-8): occupies `gridDim.x` workgroups for a given time and
+// touches no memory.  The clock is the constant-rate 100 MHz counter.  Every
+// wave leaves the loop: the counter only moves forward, and a hard cap on the
+// number of polls bounds the wait even if it did not.
+__global__ __launch_bounds__(64) void synthetic_compute_kernel(uint64_t ticks, unsigned *sink)
+{
+    const uint64_t t0 = wall_clock64();
+    uint32_t polls = 0;
+    while (wall_clock64() - t0 < ticks && polls < (1u << 24)) {
+        __builtin_amdgcn_s_sleep(32);
+        ++polls;
+    }
+    if (sink && ticks == ~0ull) *sink = polls;      // never true in practice; keeps the loop observable
+}
+
+constexpr int kEventRing = 8;
+
+}  // namespace
+
+struct pipesgd_runtime {
+    hipStream_t compute = nullptr;     // Alg. 1 "computation thread"
+    hipStream_t comm = nullptr;        // Alg. 1 "communication thread"
+    hipEvent_t local_ready[kEventRing];   // g_local[t] is ready   (compute -> comm)
+    hipEvent_t sum_ready[kEventRing];     // g_sum[t] is ready     (comm -> compute)
+    uint64_t t = 0;                    // iterations enqueued so far
+    bool ok = false;
+};
+
+extern "C" {
+
+int pipesgd_runtime_create(pipesgd_runtime **out)
+{
+    if (!out) return PIPESGD_ERR_ARG;
+    pipesgd_runtime *rt = new (std::nothrow) pipesgd_runtime();
+    if (!rt) return PIPESGD_ERR_CAPACITY;
+    bool good = hipStreamCreateWithFlags(&rt->compute, hipStreamNonBlocking) == hipSuccess &&
+                hipStreamCreateWithFlags(&rt->comm, hipStreamNonBlocking) == hipSuccess;   // default priority
+    for (int i = 0; i < kEventRing; ++i) { rt->local_ready[i] = nullptr; rt->sum_ready[i] = nullptr; }
+    for (int i = 0; good && i < kEventRing; ++i)
+        good = hipEventCreateWithFlags(&rt->local_ready[i], hipEventDisableTiming) == hipSuccess &&
+               hipEventCreateWithFlags(&rt->sum_ready[i], hipEventDisableTiming) == hipSuccess;
+    rt->ok = good;
+    if (!good) { pipesgd_runtime_destroy(rt); return PIPESGD_ERR_HIP; }
+    *out = rt;
+    return PIPESGD_OK;
+}
+
+void pipesgd_runtime_destroy(pipesgd_runtime *rt)
+{
+    if (!rt) return;
+    if (rt->compute) (void)hipStreamSynchronize(rt->compute);
+    if (rt->comm) (void)hipStreamSynchronize(rt->comm);
+    for (int i = 0; i < kEventRing; ++i) {
+        if (rt->local_ready[i]) (void)hipEventDestroy(rt->local_ready[i]);
+        if (rt->sum_ready[i]) (void)hipEventDestroy(rt->sum_ready[i]);
+    }
+    if (rt->compute) (void)hipStreamDestroy(rt->compute);
+    if (rt->comm) (void)hipStreamDestroy(rt->comm);
+    delete rt;
+}
+
+void *pipesgd_runtime_stream(pipesgd_runtime *rt, int which)
+{
+    if (!rt) return nullptr;
+    return which == 0 ? static_cast<void *>(rt->compute) : static_cast<void *>(rt->comm);
+}
+
+int pipesgd_runtime_sync(pipesgd_runtime *rt)
+{
+    if (!rt) return PIPESGD_ERR_ARG;
+    if (hipStreamSynchronize(rt->compute) != hipSuccess) return PIPESGD_ERR_HIP;
+    if (hipStreamSynchronize(rt->comm) != hipSuccess) return PIPESGD_ERR_HIP;
+    return PIPESGD_OK;
+}
+
+int pipesgd_synthetic_compute(float duration_us, int workgroups, void *stream)
+{
+    if (!(duration_us >= 0.0f) || duration_us > 1.0e6f || workgroups < 1 || workgroups > 65535) return PIPESGD_ERR_ARG;
+    if (duration_us == 0.0f) return PIPESGD_OK;
+    const uint64_t ticks = static_cast<uint64_t>(static_cast<double>(duration_us) * 100.0);   // 100 MHz
+    hipLaunchKernelGGL(synthetic_compute_kernel, dim3(workgroups), dim3(64), 0, static_cast<hipStream_t>(stream),
+                       ticks, static_cast<unsigned *>(nullptr));
+    return hipGetLastError() == hipSuccess ? PIPESGD_OK : PIPESGD_ERR_HIP;
+}
+
+int pipesgd_runtime_iteration(pipesgd_runtime *rt, const pipesgd_runtime_iter *it)
+{
+    if (!rt || !rt->ok || !it || !it->ring) return PIPESGD_ERR_ARG;
+    if ((it->width != 1 && it->width != 2) || it->reserved != 0) return PIPESGD_ERR_ARG;
+    const uint64_t t = rt->t + 1;                       // this call is iteration t (1-based)
+    hipEvent_t sum_ready = rt->sum_ready[t % kEventRing];
+    int rc;
+    const int wg = it->compute_workgroups > 0 ? it->compute_workgroups : 1;
+
+    if (it->width == 2) {
+        // Indexing: g[t] is the gradient evaluated at w[t-1]; A[t] = AllReduce(g[t]);
+        // w[t] = Update(w[t-1], A[t-1]).  (Alg. 1 counts the same steps one later.)
+        // communication thread: g[t] was marked ready by the previous call's compute part
+        if (t > 1 && hipStreamWaitEvent(rt->comm, rt->local_ready[t % kEventRing], 0) != hipSuccess) return PIPESGD_ERR_HIP;
+        rc = pipesgd_allreduce_sim(it->ring, it->schedule, rt->comm);
+        if (rc != PIPESGD_OK) return rc;
+        rc = pipesgd_synthetic_compute(it->wire_us, 1, rt->comm);          // time on the network
+        if (rc != PIPESGD_OK) return rc;
+        if (hipEventRecord(sum_ready, rt->comm) != hipSuccess) return PIPESGD_ERR_HIP;
+        // computation thread, meanwhile: wait for A[t-1], decompress + update -> w[t], then the
+        // stand-in for batch/forward/backward that yields g[t+1], and mark it ready
+        if (t > 1 && hipStreamWaitEvent(rt->compute, rt->sum_ready[(t - 1) % kEventRing], 0) != hipSuccess)
+            return PIPESGD_ERR_HIP;
+        rc = pipesgd_apply_update_multi(it->ring->mode, it->replicas, it->stale_g_sum_c, it->stale_scales, it->ring->n,
+                                        it->w, it->v, it->lr, it->momentum, it->grad_scale, rt->compute);
+        if (rc != PIPESGD_OK) return rc;
+        rc = pipesgd_synthetic_compute(it->compute_us, wg, rt->compute);
+        if (rc != PIPESGD_OK) return rc;
+        if (hipEventRecord(rt->local_ready[(t + 1) % kEventRing], rt->compute) != hipSuccess) return PIPESGD_ERR_HIP;
+    } else {
+        // decentralised synchronous SGD: compute g[t], AllReduce it, update with this iteration's sum
+        hipEvent_t local_ready = rt->local_ready[t % kEventRing];
+        rc = pipesgd_synthetic_compute(it->compute_us, wg, rt->compute);
+        if (rc != PIPESGD_OK) return rc;
+        if (hipEventRecord(local_ready, rt->compute) != hipSuccess) return PIPESGD_ERR_HIP;
+        if (hipStreamWaitEvent(rt->comm, local_ready, 0) != hipSuccess) return PIPESGD_ERR_HIP;
+        rc = pipesgd_allreduce_sim(it->ring, it->schedule, rt->comm);
+        if (rc != PIPESGD_OK) return rc;
+        rc = pipesgd_synthetic_compute(it->wire_us, 1, rt->comm);          // time on the network
+        if (rc != PIPESGD_OK) return rc;
+        if (hipEventRecord(sum_ready, rt->comm) != hipSuccess) return PIPESGD_ERR_HIP;
+        if (hipStreamWaitEvent(rt->compute, sum_ready, 0) != hipSuccess) return PIPESGD_ERR_HIP;
+        rc = pipesgd_apply_update_multi(it->ring->mode, it->replicas, it->fresh_g_sum_c, it->fresh_scales, it->ring->n,
+                                        it->w, it->v, it->lr, it->momentum, it->grad_scale, rt->compute);
+        if (rc != PIPESGD_OK) return rc;
+    }
+    rt->t = t;
+    return PIPESGD_OK;
+}
+
+}  // extern "C"

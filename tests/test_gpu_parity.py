@@ -534,3 +534,47 @@ def test_allreduce_pipelined_rejects_buckets_and_bad_arguments():
     with pytest.raises(B.PipeSgdError):
         B.allreduce_pipelined(ring, [recv[0], None], None, 2, ov)
     sync()
+
+
+# ------------------------------------------ Algorithm 1's two-thread runtime --
+
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("width", [1, 2])
+def test_two_stream_runtime_matches_oracle(orc, mode, width):
+    p, n, lr, m, iters = 4, 4096 * 11 + 77, 0.01, 0.9, 5
+    grad_fn = lambda r, w, t: W.gaussian(n, 1e-3, 21, (mode, r, t, 0))
+    w0 = W.gaussian(n, 0.05, 23)
+    sim = PipeSgdSim(mode, p, n, lr, m, 1.0, 2)          # two slot sets in both cases
+    sim.set_model(w0)
+    sync()
+    rt = B.Runtime()
+    for t in range(1, iters + 1):
+        rt.sync()                                        # gradients change: the previous AllReduce must be done
+        sim.set_gradients([grad_fn(r, None, t) for r in range(p)])
+        sync()
+        cur = t % 2
+        rt.iteration(sim.rings[cur], sim.updates[1 - cur], sim.updates[cur], B.STEPWISE, width, lr, m, 1.0,
+                     compute_us=150.0, compute_workgroups=8)
+    rt.sync()
+    ws, vs = orc.pipe_sgd_run(mode, grad_fn, w0, p, iters, lr, m, 1.0, width)
+    for r in range(p):
+        assert_fp32_close_then_exact(sim.model(r), ws[r], f"w r={r}")
+        assert_fp32_close_then_exact(sim.velocity(r), vs[r], f"v r={r}")
+    rt.close()
+
+
+def test_synthetic_compute_takes_about_the_requested_time():
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    B.synthetic_compute(50.0, 4)
+    sync()
+    for us in (200.0, 1000.0):
+        a.record()
+        B.synthetic_compute(us, 4)
+        b.record()
+        sync()
+        ms = a.elapsed_time(b)
+        assert us * 1e-3 * 0.9 <= ms <= us * 1e-3 * 1.5 + 0.05, (us, ms)
+    with pytest.raises(B.PipeSgdError):
+        B.synthetic_compute(-1.0, 4)
+    with pytest.raises(B.PipeSgdError):
+        B.synthetic_compute(10.0, 0)

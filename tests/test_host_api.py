@@ -165,3 +165,28 @@ def test_product_does_not_import_the_oracle():
         if fn.endswith((".py", ".c")):
             text = open(os.path.join(ROOT, "oracle", fn)).read()
             assert "paper_1811_03619_amd" not in text and "pipesgd.h" not in text, fn
+
+
+def test_timing_models_follow_the_papers_equations():
+    # Eq. 2-4
+    assert B.model_sync_time(100, 1.0, 5.0, 3.0) == 900.0
+    assert B.model_pipe_ideal_time(100, 2, 1.0, 5.0, 3.0) == 450.0
+    assert B.model_pipe_ideal_time(100, 1, 1.0, 5.0, 3.0) == B.model_sync_time(100, 1.0, 5.0, 3.0)
+    assert B.model_pipe_time(100, 1.0, 5.0, 3.0) == 600.0          # compute bound
+    assert B.model_pipe_time(100, 1.0, 1.0, 3.0) == 300.0          # communication bound
+    assert B.model_pipe_time(7, 0.3, 0.4, 0.2) <= B.model_sync_time(7, 0.3, 0.4, 0.2)
+    # Eq. 5: AlexNet-sized fp32 gradient over 10 Gb/s Ethernet, p = 4: the bandwidth term alone is
+    # 2 * (3/4) * 243,860,896 B / 1.25e9 B/s = 0.29263 s (half of it with 16-bit truncation)
+    n_bytes = 60_965_224 * 4
+    t = B.model_ring_comm_time(4, n_bytes, 0.0, 1 / 1.25e9, 0.0)
+    assert abs(t - 0.292633) < 1e-6
+    assert abs(B.model_ring_comm_time(4, n_bytes / 2, 0.0, 1 / 1.25e9, 0.0) - t / 2) < 1e-12
+    # all four terms: 2(p-1) alpha + 2((p-1)/p) n beta + ((p-1)/p) n gamma + S
+    assert abs(B.model_ring_comm_time(4, 1000.0, 1e-3, 1e-6, 2e-6, 5e-3) - (6e-3 + 1.5e-3 + 1.5e-3 + 5e-3)) < 1e-15
+    # Eq. 6 with L segments pays the latency and the synchronisation L times; L = 1 is Eq. 5
+    e5 = B.model_ring_comm_time(8, 1e6, 1e-4, 1e-9, 1e-10, 1e-4, 1)
+    e6 = B.model_ring_comm_time(8, 1e6, 1e-4, 1e-9, 1e-10, 1e-4, 4)
+    assert abs((e6 - e5) - (3 * (2 * 7 * 1e-4 + 1e-4))) < 1e-15
+    # Eq. 7
+    assert B.model_scaling_efficiency(1.0, 5.0, 3.0) == 1.0
+    assert B.model_scaling_efficiency(1.0, 1.0, 4.0) == 0.5
