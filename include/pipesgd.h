@@ -11,7 +11,9 @@
  *   - Return value: 0 on success, a negative PIPESGD_ERR_* otherwise.  Nothing
  *     throws, aborts or logs.  On error nothing has been enqueued.
  *   - "DEVICE" pointers are HIP device memory owned by the caller; the library
- *     allocates no device memory and keeps no state between calls.  "HOST"
+ *     allocates no device memory.  The only state it keeps is on the host: the
+ *     launch-geometry table (see "tuning") and what the opaque pipesgd_overlap
+ *     and pipesgd_runtime objects hold (HIP events, two streams).  "HOST"
  *     pointers are ordinary host memory read during the call only.
  *   - Every DEVICE pointer must be 16-byte aligned.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
