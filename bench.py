@@ -56,13 +56,18 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=3, help="workload 1..5 (3 = AlexNet-shaped, 61M, the headline)")
     ap.add_argument("--mode", type=int, default=None, help="override compression mode 0/1/2")
-    ap.add_argument("--schedule", choices=["stepwise", "fused"], default="stepwise")
+    ap.add_argument("--schedule", choices=["stepwise", "fused", "one-launch"], default="stepwise",
+                    help="stepwise: one launch per ring round, every hop payload in memory (the headline); fused: the "
+                         "AllReduce in one launch; one-launch: AllReduce and update of an iteration in one launch")
     ap.add_argument("--workers", type=int, default=4)
     ap.add_argument("--lr", type=float, default=0.01)
     ap.add_argument("--momentum", type=float, default=None)
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle timing (0 = skip)")
     ap.add_argument("--phases", action="store_true", help="also time each phase separately")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay the iterations from a captured HIP graph (two iterations per replay); "
+                         "the update kernel is then not bracketed by events, so roofline.achieved is null")
     ap.add_argument("--study", choices=["within-allreduce", "two-thread-runtime"], default=None,
                     help="extra measurement printed as its own JSON line after the main one")
     ap.add_argument("--calib-copy", type=int, default=0,
@@ -90,7 +95,7 @@ def main() -> int:
     cfg, p = args.config, args.workers
     mode = MODE_OF_CONFIG[cfg] if args.mode is None else args.mode
     momentum = (0.0 if cfg == 1 else 0.9) if args.momentum is None else args.momentum
-    schedule = B.STEPWISE if args.schedule == "stepwise" else B.FUSED
+    schedule = {"stepwise": B.STEPWISE, "fused": B.FUSED, "one-launch": B.ONE_LAUNCH}[args.schedule]
 
     specs = W.config_tensors(cfg)
     numels = [s.numel for s in specs]
@@ -122,28 +127,49 @@ def main() -> int:
 
     # ---- timed region: exactly `steps` iterations; the update launch of every
     # iteration is bracketed by events on the launch stream for the roofline.
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-    start_ev, stop_ev = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    t_begin = time.perf_counter()
-    start_ev.record()
-    for i in range(args.steps):
-        cur = sim.allreduce()
-        ev[i][0].record()
-        sim.update_from(1 - cur)
-        ev[i][1].record()
-        sim.t += 1
-    stop_ev.record()
-    torch.cuda.synchronize()
-    wall_s = time.perf_counter() - t_begin
+    upd_ms = None
+    if args.graph:
+        if args.steps % 2 or sim.t % 2:
+            print("bench.py: --graph replays pairs of iterations: use even --steps and --warmup", file=sys.stderr)
+            return 2
+        graph = sim.capture_pair()
+        graph.replay()
+        torch.cuda.synchronize()
+        start_ev, stop_ev = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t_begin = time.perf_counter()
+        start_ev.record()
+        for _ in range(args.steps // 2):
+            graph.replay()
+        stop_ev.record()
+        torch.cuda.synchronize()
+        wall_s = time.perf_counter() - t_begin
+    else:
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+        start_ev, stop_ev = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t_begin = time.perf_counter()
+        start_ev.record()
+        if schedule == B.ONE_LAUNCH:
+            for i in range(args.steps):
+                sim.iteration()
+        else:
+            for i in range(args.steps):
+                cur = sim.allreduce()
+                ev[i][0].record()
+                sim.update_from(1 - cur)
+                ev[i][1].record()
+                sim.t += 1
+        stop_ev.record()
+        torch.cuda.synchronize()
+        wall_s = time.perf_counter() - t_begin
+        upd_ms = float(np.mean([a.elapsed_time(b) for a, b in ev])) if schedule != B.ONE_LAUNCH else None
     ms_per_step = wall_s * 1e3 / args.steps
     gpu_ms_per_step = start_ev.elapsed_time(stop_ev) / args.steps
-    upd_ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
 
     n_true = int(sum(numels))          # bucket padding is processed but is not part of the model
-    model = bytes_model(mode, n_true, p, momentum != 0.0, fused=(schedule == B.FUSED))
+    model = bytes_model(mode, n_true, p, momentum != 0.0, fused=(schedule != B.STEPWISE))
     value = model["total"] / (ms_per_step * 1e-3) / 1e9
-    upd_gbs = model["update"] / (upd_ms * 1e-3) / 1e9
+    upd_gbs = model["update"] / (upd_ms * 1e-3) / 1e9 if upd_ms else None
 
     traffic = committed_traffic(cfg, ["none", "trunc16", "quant8"][mode])
 
@@ -165,7 +191,7 @@ def main() -> int:
             "packed_elements_per_worker": n,
             "tensors": len(specs), "buckets": len(buckets) if buckets else 1,
             "compression": ["none", "trunc16", "quant8"][mode], "momentum": momentum, "lr": args.lr,
-            "pipeline_width": 2, "schedule": args.schedule, "seed": args.seed,
+            "pipeline_width": 2, "schedule": args.schedule, "hip_graph": bool(args.graph), "seed": args.seed,
         },
         "iters_per_s": round(1e3 / ms_per_step, 2),
         "hbm_peak_fraction": round(value / HBM_PEAK_GBS, 4),
@@ -173,9 +199,9 @@ def main() -> int:
         "bytes_per_iter": {k: int(v) for k, v in model.items()},
         "roofline": {
             "kernel": "update_kernel (decompress + momentum-SGD, all replicas, one launch)",
-            "bound": "hbm", "achieved": round(upd_gbs, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": round(upd_gbs / HBM_PEAK_GBS, 4), "traffic": traffic,
-            "launch_ms": round(upd_ms, 5), "algorithmic_bytes_per_launch": int(model["update"]),
+            "bound": "hbm", "achieved": round(upd_gbs, 2) if upd_gbs else None, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": round(upd_gbs / HBM_PEAK_GBS, 4) if upd_gbs else None, "traffic": traffic,
+            "launch_ms": round(upd_ms, 5) if upd_ms else None, "algorithmic_bytes_per_launch": int(model["update"]),
         },
         "input_generation_s": round(gen_s, 2),
     }

@@ -215,6 +215,19 @@ int pipesgd_apply_update_multi(int mode, int replicas, const void *const *g_sum_
                                float *const *v, float lr, float momentum, float grad_scale,
                                void *stream);
 
+/* One whole width-2 iteration in a single launch: the AllReduce of ring->g_local
+ * into ring->g_sum_c (fused schedule) together with the update of all
+ * ring->workers replicas from the PREVIOUS iteration's slot set `stale_*`.  The
+ * two halves touch disjoint buffers (the independence the paper's pipeline rests
+ * on), so they share one grid.  For gradients so small that launch latency sets
+ * the pace (a few MB, or many small buckets).  Same result bits as
+ * pipesgd_allreduce_sim + pipesgd_apply_update_multi.  `stale_*`, w, v: HOST
+ * arrays of ring->workers DEVICE pointers; the stale slot set must not be the
+ * one the ring writes (PIPESGD_ERR_ARG). */
+int pipesgd_iteration_fused(const pipesgd_ring *ring, const void *const *stale_g_sum_c,
+                            const float *const *stale_scales, float *const *w, float *const *v,
+                            float lr, float momentum, float grad_scale, void *stream);
+
 /* -------------------------------------------------------------- bucketing -- */
 
 /* Small-tensor fusion (not in the paper, which sends the gradient as one

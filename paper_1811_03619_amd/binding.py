@@ -15,6 +15,7 @@ from . import buildlib
 
 NONE, TRUNC16, QUANT8 = 0, 1, 2
 STEPWISE, FUSED = 0, 1
+ONE_LAUNCH = 2          # pipeline.PipeSgdSim only: pipesgd_iteration_fused
 MAX_WORKERS = 16
 MAX_BUCKETS = 64
 QBLOCK = 4096
@@ -30,7 +31,7 @@ EXPORTS = [
     "pipesgd_runtime_create", "pipesgd_runtime_destroy", "pipesgd_runtime_iteration", "pipesgd_runtime_sync",
     "pipesgd_runtime_stream", "pipesgd_synthetic_compute",
     "pipesgd_model_sync_time", "pipesgd_model_pipe_ideal_time", "pipesgd_model_pipe_time",
-    "pipesgd_model_ring_comm_time", "pipesgd_model_scaling_efficiency",
+    "pipesgd_model_ring_comm_time", "pipesgd_model_scaling_efficiency", "pipesgd_iteration_fused",
 ]
 K_FIRST_SEND, K_REDUCE_SCATTER, K_ALLGATHER, K_FUSED, K_UPDATE, K_COMPRESS, K_DECOMPRESS = range(7)
 
@@ -152,6 +153,8 @@ def lib():
         getattr(L, name).argtypes = [dbl] * nargs
     L.pipesgd_model_ring_comm_time.restype = dbl
     L.pipesgd_model_ring_comm_time.argtypes = [i32, dbl, dbl, dbl, dbl, dbl, i32]
+    L.pipesgd_iteration_fused.restype = i32
+    L.pipesgd_iteration_fused.argtypes = [C.POINTER(RingStruct), vp, vp, vp, vp, f32, f32, f32, vp]
     L.pipesgd_set_launch_config.restype = i32
     L.pipesgd_set_launch_config.argtypes = [i32, i32, i32, i32, i32]
     L.pipesgd_get_launch_config.restype = i32
@@ -392,6 +395,12 @@ def model_ring_comm_time(p, n_bytes, alpha, beta, gamma, S=0.0, L=1):
 
 def model_scaling_efficiency(l_up, l_comp, l_comm):
     return lib().pipesgd_model_scaling_efficiency(l_up, l_comp, l_comm)
+
+
+def iteration_fused(ring: RingStruct, stale: UpdateArgs, lr: float, momentum: float = 0.0,
+                    grad_scale: float = 1.0, stream=None) -> None:
+    check(lib().pipesgd_iteration_fused(C.byref(ring), stale.g_sum_c, stale.scales, stale.w, stale.v,
+                                        lr, momentum, grad_scale, _stream(stream)), "pipesgd_iteration_fused")
 
 
 def bucket_plan(numels: Sequence[int], bucket_elems: int = 1 << 20, max_buckets: int = MAX_BUCKETS):

@@ -646,6 +646,36 @@ __global__ __launch_bounds__(G::kThreads) void update_kernel(UpdateArgs a)
     else        update_body<MODE, MOMENTUM, G, false>(a, t, r, scale);
 }
 
+// A whole width-2 iteration in ONE launch, for gradients so small that launch
+// latency, not bandwidth, sets the pace: the AllReduce of this iteration's
+// gradients (chain in registers, as in ring_fused_kernel) and the update from
+// the previous iteration's slot touch disjoint buffers (that independence is
+// the paper's pipeline), so they can share a grid.  Workgroups with
+// blockIdx.x < ring_blocks walk a ring unit of chunk blockIdx.y, the others
+// update a unit of replica blockIdx.y.
+template <int MODE, bool MOMENTUM>
+__global__ __launch_bounds__(256) void iteration_fused_kernel(RingArgs a, BucketTable bt, UpdateArgs u, uint32_t ring_blocks)
+{
+    using G = Geo<256, 4>;
+    __shared__ float red[2][G::kWaves];
+    if (blockIdx.x < ring_blocks) {
+        const int c = blockIdx.y;
+        if (c >= a.p) return;
+        const UnitRef t = locate<G>(bt, blockIdx.x, c);
+        if (t.empty) return;
+        if (t.full) ring_fused_body<MODE, G, true>(a, t, c, red);
+        else        ring_fused_body<MODE, G, false>(a, t, c, red);
+    } else {
+        const int r = blockIdx.y;
+        const uint32_t unit = blockIdx.x - ring_blocks;
+        if (static_cast<uint64_t>(unit) * G::kUnit >= u.n) return;
+        const UnitRef t = locate_flat<G>(u.n, unit);
+        const float scale = MODE == PIPESGD_QUANT8 ? u.sc[r][t.elem0 / kTile] : 0.0f;
+        if (t.full) update_body<MODE, MOMENTUM, G, true>(u, t, r, scale);
+        else        update_body<MODE, MOMENTUM, G, false>(u, t, r, scale);
+    }
+}
+
 // Many tensor <-> packed-buffer copies in one launch.  The segment table is in
 // device memory; a block finds its segment by binary search on first_tile.
 template <bool TO_PACKED>
@@ -1187,10 +1217,8 @@ int pipesgd_allreduce_pipelined(const pipesgd_ring *ring, void *const *recv, flo
     return PIPESGD_OK;
 }
 
-int pipesgd_apply_update_multi(int mode, int replicas, const void *const *g_sum_c,
-                               const float *const *scales, uint64_t n, float *const *w,
-                               float *const *v, float lr, float momentum, float grad_scale,
-                               void *stream)
+static int prepare_update(int mode, int replicas, const void *const *g_sum_c, const float *const *scales, uint64_t n,
+                          float *const *w, float *const *v, float lr, float momentum, float grad_scale, UpdateArgs &ua)
 {
     if (!mode_ok(mode)) return PIPESGD_ERR_MODE;
     if (replicas < 1) return PIPESGD_ERR_ARG;
@@ -1199,10 +1227,8 @@ int pipesgd_apply_update_multi(int mode, int replicas, const void *const *g_sum_
     const bool mom = momentum != 0.0f;
     if (mom && !v) return PIPESGD_ERR_ARG;
     if (mode == PIPESGD_QUANT8 && !scales) return PIPESGD_ERR_ARG;
-    if (n == 0) return PIPESGD_OK;
-    UpdateArgs ua;
     for (int r = 0; r < kMaxW; ++r) { ua.pay[r] = nullptr; ua.sc[r] = nullptr; ua.w[r] = nullptr; ua.v[r] = nullptr; }
-    for (int r = 0; r < replicas; ++r) {
+    for (int r = 0; r < replicas && n > 0; ++r) {
         if (!g_sum_c[r] || !w[r] || (mom && !v[r]) || (mode == PIPESGD_QUANT8 && !scales[r])) return PIPESGD_ERR_ARG;
         if (!aligned16(g_sum_c[r]) || !aligned16(w[r]) || (mom && !aligned16(v[r])) ||
             (mode == PIPESGD_QUANT8 && !aligned16(scales[r])))
@@ -1213,12 +1239,53 @@ int pipesgd_apply_update_multi(int mode, int replicas, const void *const *g_sum_
         ua.v[r] = mom ? v[r] : nullptr;
     }
     ua.n = n; ua.lr = lr; ua.momentum = momentum; ua.grad_scale = grad_scale;
+    return PIPESGD_OK;
+}
+
+int pipesgd_apply_update_multi(int mode, int replicas, const void *const *g_sum_c,
+                               const float *const *scales, uint64_t n, float *const *w,
+                               float *const *v, float lr, float momentum, float grad_scale,
+                               void *stream)
+{
+    UpdateArgs ua;
+    const int rc = prepare_update(mode, replicas, g_sum_c, scales, n, w, v, lr, momentum, grad_scale, ua);
+    if (rc != PIPESGD_OK) return rc;
+    if (n == 0) return PIPESGD_OK;
+    const bool mom = momentum != 0.0f;
     const LaunchConfig c = g_cfg[kUpdate][mode];
     hipStream_t s = static_cast<hipStream_t>(stream);
 #define CALL(M) return mom ? launch_update<M, true>(c, ua, replicas, s) : launch_update<M, false>(c, ua, replicas, s);
     PIPESGD_MODE_SWITCH(mode, CALL)
 #undef CALL
     return PIPESGD_ERR_MODE;
+}
+
+int pipesgd_iteration_fused(const pipesgd_ring *ring, const void *const *stale_g_sum_c,
+                            const float *const *stale_scales, float *const *w, float *const *v,
+                            float lr, float momentum, float grad_scale, void *stream)
+{
+    RingArgs ra; BucketTable bt; uint64_t slots = 0;
+    int rc = prepare_ring(ring, ra, bt, slots);
+    if (rc != PIPESGD_OK) return rc;
+    UpdateArgs ua;
+    rc = prepare_update(ring->mode, ring->workers, stale_g_sum_c, stale_scales, ring->n, w, v, lr, momentum, grad_scale, ua);
+    if (rc != PIPESGD_OK) return rc;
+    if (ring->n == 0) return PIPESGD_OK;
+    for (int r = 0; r < ring->workers; ++r)                 // the two halves must not touch the same slot set
+        for (int q = 0; q < ring->workers; ++q)
+            if (stale_g_sum_c[r] == ring->g_sum_c[q]) return PIPESGD_ERR_ARG;
+    const uint64_t upd_units = (ring->n + kTile - 1) / kTile;
+    if (slots + upd_units > 0x7fffffffull) return PIPESGD_ERR_CAPACITY;
+    const dim3 grid(static_cast<uint32_t>(slots + upd_units), ring->workers);
+    const uint32_t ring_blocks = static_cast<uint32_t>(slots);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const bool mom = momentum != 0.0f;
+#define CALL(M)                                                                                                        \
+    if (mom) hipLaunchKernelGGL((iteration_fused_kernel<M, true>), grid, dim3(256), 0, s, ra, bt, ua, ring_blocks);    \
+    else     hipLaunchKernelGGL((iteration_fused_kernel<M, false>), grid, dim3(256), 0, s, ra, bt, ua, ring_blocks);
+    PIPESGD_MODE_SWITCH(ring->mode, CALL)
+#undef CALL
+    return hipGetLastError() == hipSuccess ? PIPESGD_OK : PIPESGD_ERR_HIP;
 }
 
 int pipesgd_apply_update(int mode, const void *g_sum_c, const float *scales, uint64_t n,

@@ -88,16 +88,37 @@ class PipeSgdSim:
     def allreduce(self, stream=None) -> int:
         """Enqueue the AllReduce of the current gradients; returns the slot index."""
         i = (self.t + 1) % len(self.rings)
-        B.allreduce_sim(self.rings[i], self.schedule, stream)
+        B.allreduce_sim(self.rings[i], B.FUSED if self.schedule == B.ONE_LAUNCH else self.schedule, stream)
         self._last = i
         return i
 
     def update_from(self, slot: int, stream=None) -> None:
         B.apply_update_multi(self.mode, self.updates[slot], self.n, self.lr, self.momentum, self.grad_scale, stream)
 
+    def capture_pair(self):
+        """Record two consecutive iterations (one ping and one pong of the slot
+        sets) into a HIP graph and return it; ``graph.replay()`` then enqueues
+        both with one host call.  Launch-bound (small or many-bucket) models are
+        limited by per-launch host and queue latency, not by the kernels.  The
+        library's calls only launch kernels (no memset, no allocation), so they
+        capture as they are; warm the kernels up once before capturing."""
+        assert self.width == 2 and self.t % 2 == 0, "capture at an even iteration count"
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            self.iteration()
+            self.iteration()
+        return g
+
     def iteration(self, stream=None) -> None:
         """One pass of the hot path: AllReduce of g_local[t] and the update that
         yields w[t] (from the previous AllReduce's slot when width is 2)."""
+        if self.schedule == B.ONE_LAUNCH:
+            assert self.width == 2
+            cur = (self.t + 1) % 2
+            B.iteration_fused(self.rings[cur], self.updates[1 - cur], self.lr, self.momentum, self.grad_scale, stream)
+            self._last = cur
+            self.t += 1
+            return
         cur = self.allreduce(stream)
         if self.width == 2:
             self.update_from(1 - cur, stream)

@@ -578,3 +578,76 @@ def test_synthetic_compute_takes_about_the_requested_time():
         B.synthetic_compute(-1.0, 4)
     with pytest.raises(B.PipeSgdError):
         B.synthetic_compute(10.0, 0)
+
+
+# ---------------------------------------------------------------- HIP graph --
+
+@pytest.mark.parametrize("mode,bucketed", [(B.NONE, False), (B.TRUNC16, True), (B.QUANT8, False)])
+def test_graph_replay_equals_eager(orc, mode, bucketed):
+    # two iterations captured into one graph; several replays, with eager work
+    # and synchronisations in between, each checked against the oracle
+    p, lr, m = 4, 0.01, 0.9
+    if bucketed:
+        specs = W.scaled_config(5, 8)
+        numels = [s.numel for s in specs]
+        buckets, offs, n = B.bucket_plan(numels, 1 << 16)
+        grads = [orc.pack(W.gradient_tensors_for(specs, 5, r, seed=11), offs, n) for r in range(p)]
+    else:
+        buckets, n = None, 4096 * 13 + 99
+        grads = [W.gaussian(n, 1e-3, 11, (mode, r, 0, 0)) for r in range(p)]
+    w0 = W.gaussian(n, 0.05, 13)
+    sim = PipeSgdSim(mode, p, n, lr, m, 1.0, 2, buckets)
+    sim.set_gradients(grads)
+    sim.set_model(w0)
+    sim.iteration(); sim.iteration()                 # warm-up, eager: t = 2
+    sync()
+    graph = sim.capture_pair()
+    scratch = torch.zeros(1 << 20, device="cuda:0")
+    total = 2
+    for rep in range(3):
+        graph.replay()
+        total += 2
+        scratch.add_(1.0)                            # unrelated eager work between replays
+        sync()
+        ws, vs = orc.pipe_sgd_run(mode, lambda r, w, t: grads[r], w0, p, total, lr, m, 1.0, 2, buckets)
+        for r in range(p):
+            assert_fp32_close_then_exact(sim.model(r), ws[r], f"w r={r} after replay {rep}")
+            assert_fp32_close_then_exact(sim.velocity(r), vs[r], f"v r={r} after replay {rep}")
+    assert float(scratch[0]) == 3.0
+
+
+# ------------------------------------------------ one launch per iteration --
+
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("momentum", [0.0, 0.9])
+@pytest.mark.parametrize("bucketed", [False, True])
+def test_one_launch_iteration_equals_oracle(orc, mode, momentum, bucketed):
+    p, lr, iters = 4, 0.01, 4
+    if bucketed:
+        specs = W.scaled_config(5, 8)
+        numels = [s.numel for s in specs]
+        buckets, offs, n = B.bucket_plan(numels, 1 << 16)
+        grad_fn = lambda r, w, t: orc.pack(W.gradient_tensors_for(specs, 5, r, seed=31, iteration=t), offs, n)
+    else:
+        buckets, n = None, 4096 * 6 + 1001
+        grad_fn = lambda r, w, t: W.gaussian(n, 1e-3, 31, (mode, r, t, 0))
+    w0 = W.gaussian(n, 0.05, 33)
+    sim, ws_ref, vs_ref = run_both(orc, mode, grad_fn, w0, p, iters, lr, momentum, 2, buckets, B.ONE_LAUNCH)
+    for r in range(p):
+        assert_fp32_close_then_exact(sim.model(r), ws_ref[r], f"w r={r}")
+        assert_fp32_close_then_exact(sim.velocity(r), vs_ref[r], f"v r={r}")
+    last = [grad_fn(r, None, iters) for r in range(p)]
+    want = orc.allreduce_bucketed(mode, last, buckets) if buckets else orc.allreduce(mode, last)
+    for r in range(p):
+        pay, sc = sim.result(r)
+        assert_bits_equal(pay, want[r][0], f"payload r={r}")
+        if mode == B.QUANT8:
+            assert_bits_equal(sc, want[r][1], f"scales r={r}")
+
+
+def test_one_launch_iteration_rejects_aliased_slots():
+    n = 4096 * 2
+    sim = PipeSgdSim(B.TRUNC16, 2, n, 0.01, 0.9)
+    with pytest.raises(B.PipeSgdError):
+        B.iteration_fused(sim.rings[0], sim.updates[0], 0.01, 0.9)
+    sync()
