@@ -32,13 +32,20 @@ def payload_bytes_per_elem(mode: int) -> float:
     return {0: 4.0, 1: 2.0, 2: 1.0 + 4.0 / 4096.0}[mode]
 
 
-def bytes_model(mode: int, n: int, p: int, momentum: bool, fused: bool = False):
+def bytes_model(mode: int, n: int, p: int, momentum: bool, fused: bool = False, direct: bool = False):
     """Algorithmic bytes of one iteration, by phase.  Stepwise schedule: every
     hop's payload is written once and read once.  Fused schedule: each gradient
     is read once and each worker's result written once (hop payloads never
     reach memory), so it is priced with its own, smaller byte count."""
     cb = payload_bytes_per_elem(mode)
     upd = p * n * (cb + (16.0 if momentum else 8.0))
+    if direct:
+        # exchange 1: every worker reads (p-1)/p of its gradient and writes it compressed; owner: reads its
+        # block and p-1 payloads, writes the result into p slots
+        scatter = (p - 1) * (4.0 + cb) * n
+        reduce_bcast = (4.0 + (p - 1) * cb + p * cb) * n
+        return {"direct_scatter": scatter, "direct_reduce_broadcast": reduce_bcast, "update": upd,
+                "total": scatter + reduce_bcast + upd}
     if fused:
         ar = (4.0 * p + cb * p) * n
         return {"allreduce_fused": ar, "update": upd, "total": ar + upd}
@@ -56,7 +63,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=3, help="workload 1..5 (3 = AlexNet-shaped, 61M, the headline)")
     ap.add_argument("--mode", type=int, default=None, help="override compression mode 0/1/2")
-    ap.add_argument("--schedule", choices=["stepwise", "fused", "one-launch"], default="stepwise",
+    ap.add_argument("--schedule", choices=["stepwise", "fused", "one-launch", "direct"], default="stepwise",
                     help="stepwise: one launch per ring round, every hop payload in memory (the headline); fused: the "
                          "AllReduce in one launch; one-launch: AllReduce and update of an iteration in one launch")
     ap.add_argument("--workers", type=int, default=4)
@@ -95,7 +102,7 @@ def main() -> int:
     cfg, p = args.config, args.workers
     mode = MODE_OF_CONFIG[cfg] if args.mode is None else args.mode
     momentum = (0.0 if cfg == 1 else 0.9) if args.momentum is None else args.momentum
-    schedule = {"stepwise": B.STEPWISE, "fused": B.FUSED, "one-launch": B.ONE_LAUNCH}[args.schedule]
+    schedule = {"stepwise": B.STEPWISE, "fused": B.FUSED, "one-launch": B.ONE_LAUNCH, "direct": B.DIRECT}[args.schedule]
 
     specs = W.config_tensors(cfg)
     numels = [s.numel for s in specs]
@@ -167,7 +174,7 @@ def main() -> int:
     gpu_ms_per_step = start_ev.elapsed_time(stop_ev) / args.steps
 
     n_true = int(sum(numels))          # bucket padding is processed but is not part of the model
-    model = bytes_model(mode, n_true, p, momentum != 0.0, fused=(schedule != B.STEPWISE))
+    model = bytes_model(mode, n_true, p, momentum != 0.0, fused=(schedule in (B.FUSED, B.ONE_LAUNCH)), direct=(schedule == B.DIRECT))
     value = model["total"] / (ms_per_step * 1e-3) / 1e9
     upd_gbs = model["update"] / (upd_ms * 1e-3) / 1e9 if upd_ms else None
 

@@ -160,6 +160,21 @@ int pipesgd_ring_allgather_step(const pipesgd_ring *ring, int step, void *stream
  * bytes moved, for launch-bound (small or many-bucket) gradients. */
 int pipesgd_allreduce_sim(const pipesgd_ring *ring, int schedule, void *stream);
 
+/* A second AllReduce schedule, the one-exchange ("direct") schedule -- what an
+ * 8-GPU node with a direct link between every pair of GPUs would run instead
+ * of a ring (Sec. 3.1 notes that its analysis carries over to other AllReduce
+ * algorithms).  Worker j owns chunk j.  Exchange 1: every worker k compresses
+ * chunk j of its gradient for every j != k (into stage[k], its send buffer).
+ * Owner j then computes  P = g_j[j];  P = P + D(stage[(j+d) mod p][j]) for
+ * d = 1..p-1 in this order;  and, exchange 2, writes C(P) into all p result
+ * slots.  Two launches, two exchanges instead of 2(p-1), the same volume on the
+ * links, and every value passes the codec twice instead of p times (less loss
+ * than the ring; with PIPESGD_NONE the result bits equal the ring's).
+ * stage / stage_scales: HOST arrays of p DEVICE buffers, each as large as a
+ * result slot; contents are scratch.  Buckets are supported. */
+int pipesgd_allreduce_direct(const pipesgd_ring *ring, void *const *stage, float *const *stage_scales,
+                             void *stream);
+
 /* ---------------------------------------- pipelining within the AllReduce -- */
 
 /* Host-side resources (HIP events) of the two-stream schedule below.  No device

@@ -313,6 +313,50 @@ void orc_allreduce(int mode, int p, size_t n, const float *const *g_local,
     orc_ring_free(R);
 }
 
+/* ------------------------------------------------ direct (one-exchange) -- */
+
+/* A second AllReduce schedule with the same definition of the result (Sec. 3.1
+ * notes that its conclusions carry over to other AllReduce algorithms): every
+ * worker is the owner of one block.  Round 1: worker k sends the compressed
+ * block j of its gradient straight to owner j, for every j != k.  The owner
+ * starts from its own full-precision block and adds the decompressed
+ * contributions in the order of increasing ring distance (j+1, j+2, ...), then
+ * compresses once.  Round 2: the owner sends the compressed result to everyone.
+ * Two rounds instead of 2(p-1), the same volume, and every value goes through
+ * the codec twice instead of p times.  counters (may be NULL): [0] rounds,
+ * [1] elements sent by worker 0, [2] elements reduced by worker 0. */
+void orc_allreduce_direct(int mode, int p, size_t n, const float *const *g_local,
+                          void *const *out_payload, float *const *out_scales, uint64_t *counters)
+{
+    size_t ce = orc_chunk_elems(n, p);
+    float *P = (float *)malloc((ce + 1) * sizeof(float));
+    float *tmp = (float *)malloc((ce + 1) * sizeof(float));
+    void *msg = malloc(orc_payload_bytes(mode, ce) + 1);
+    float *msg_sc = (float *)malloc((orc_num_scales(mode, ce) + 1) * sizeof(float));
+    uint64_t sent0 = 0, reduced0 = 0;
+    for (int j = 0; j < p; ++j) {                       /* owner j, block j */
+        size_t lo = chunk_lo(n, ce, j), hi = chunk_hi(n, ce, j), len = hi - lo;
+        for (size_t i = 0; i < len; ++i) P[i] = g_local[j][lo + i];
+        for (int d = 1; d < p; ++d) {
+            int k = modp(j + d, p);
+            orc_compress(mode, g_local[k] + lo, len, msg, msg_sc);      /* round 1: k -> j */
+            orc_decompress(mode, msg, msg_sc, len, tmp);
+            for (size_t i = 0; i < len; ++i) P[i] = P[i] + tmp[i];
+            if (k == 0) sent0 += len;
+            if (j == 0) reduced0 += len;
+        }
+        orc_compress(mode, P, len, msg, msg_sc);
+        for (int r = 0; r < p; ++r) {                   /* round 2: j -> everyone (and its own copy) */
+            memcpy((char *)out_payload[r] + orc_payload_bytes(mode, lo), msg, orc_payload_bytes(mode, len));
+            size_t ns = orc_num_scales(mode, len);
+            if (ns) memcpy(out_scales[r] + lo / ORC_QBLOCK, msg_sc, ns * 4);
+        }
+        if (j == 0) sent0 += (uint64_t)(p - 1) * len;
+    }
+    if (counters) { counters[0] = p > 1 ? 2 : 0; counters[1] = sent0; counters[2] = reduced0; }
+    free(P); free(tmp); free(msg); free(msg_sc);
+}
+
 /* --------------------------------------------------------------- update -- */
 
 /* Alg. 1 compute thread, lines 4-5, for one model replica: decompress the

@@ -79,6 +79,8 @@ def lib():
             getattr(L, name).argtypes = [vp, i32]
         L.orc_allreduce.restype = None
         L.orc_allreduce.argtypes = [i32, i32, sz, vp, vp, vp]
+        L.orc_allreduce_direct.restype = None
+        L.orc_allreduce_direct.argtypes = [i32, i32, sz, vp, vp, vp, vp]
         L.orc_sgd_update.restype = None
         L.orc_sgd_update.argtypes = [i32, vp, vp, sz, vp, vp, f32, f32, f32]
         _lib = L
@@ -227,6 +229,19 @@ def allreduce(mode: int, g_local: Sequence[np.ndarray]):
     pays = [np.zeros(n, dtype=_PAYLOAD_DTYPE[mode]) for _ in range(p)]
     scs = [np.zeros(num_scales(mode, n), dtype=np.float32) if mode == QUANT8 else None for _ in range(p)]
     lib().orc_allreduce(mode, p, n, _ptr_array(g), _ptr_array(pays), _ptr_array(scs))
+    return list(zip(pays, scs))
+
+
+def allreduce_direct(mode: int, g_local: Sequence[np.ndarray], counters: Optional[np.ndarray] = None):
+    """The one-exchange schedule: every block is reduced on its owner from the
+    other workers' compressed blocks and sent back once.  Same return shape as
+    ``allreduce``.  ``counters``: optional uint64[3] (rounds, elements sent by
+    worker 0, elements reduced by worker 0)."""
+    g = [_f32(x).ravel() for x in g_local]
+    p, n = len(g), g[0].size
+    pays = [np.zeros(n, dtype=_PAYLOAD_DTYPE[mode]) for _ in range(p)]
+    scs = [np.zeros(num_scales(mode, n), dtype=np.float32) if mode == QUANT8 else None for _ in range(p)]
+    lib().orc_allreduce_direct(mode, p, n, _ptr_array(g), _ptr_array(pays), _ptr_array(scs), _ptr(counters))
     return list(zip(pays, scs))
 
 

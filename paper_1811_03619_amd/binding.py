@@ -16,6 +16,7 @@ from . import buildlib
 NONE, TRUNC16, QUANT8 = 0, 1, 2
 STEPWISE, FUSED = 0, 1
 ONE_LAUNCH = 2          # pipeline.PipeSgdSim only: pipesgd_iteration_fused
+DIRECT = 3              # pipeline.PipeSgdSim only: pipesgd_allreduce_direct
 MAX_WORKERS = 16
 MAX_BUCKETS = 64
 QBLOCK = 4096
@@ -31,7 +32,7 @@ EXPORTS = [
     "pipesgd_runtime_create", "pipesgd_runtime_destroy", "pipesgd_runtime_iteration", "pipesgd_runtime_sync",
     "pipesgd_runtime_stream", "pipesgd_synthetic_compute",
     "pipesgd_model_sync_time", "pipesgd_model_pipe_ideal_time", "pipesgd_model_pipe_time",
-    "pipesgd_model_ring_comm_time", "pipesgd_model_scaling_efficiency", "pipesgd_iteration_fused",
+    "pipesgd_model_ring_comm_time", "pipesgd_model_scaling_efficiency", "pipesgd_iteration_fused", "pipesgd_allreduce_direct",
 ]
 K_FIRST_SEND, K_REDUCE_SCATTER, K_ALLGATHER, K_FUSED, K_UPDATE, K_COMPRESS, K_DECOMPRESS = range(7)
 
@@ -153,6 +154,8 @@ def lib():
         getattr(L, name).argtypes = [dbl] * nargs
     L.pipesgd_model_ring_comm_time.restype = dbl
     L.pipesgd_model_ring_comm_time.argtypes = [i32, dbl, dbl, dbl, dbl, dbl, i32]
+    L.pipesgd_allreduce_direct.restype = i32
+    L.pipesgd_allreduce_direct.argtypes = [C.POINTER(RingStruct), vp, vp, vp]
     L.pipesgd_iteration_fused.restype = i32
     L.pipesgd_iteration_fused.argtypes = [C.POINTER(RingStruct), vp, vp, vp, vp, f32, f32, f32, vp]
     L.pipesgd_set_launch_config.restype = i32
@@ -264,6 +267,12 @@ def ring_allgather_step(ring: RingStruct, step: int, stream=None) -> None:
 
 def allreduce_sim(ring: RingStruct, schedule: int = STEPWISE, stream=None) -> None:
     check(lib().pipesgd_allreduce_sim(C.byref(ring), schedule, _stream(stream)), "pipesgd_allreduce_sim")
+
+
+def allreduce_direct(ring: RingStruct, stage: Sequence, stage_scales: Optional[Sequence], stream=None) -> None:
+    check(lib().pipesgd_allreduce_direct(C.byref(ring), _ptr_array(stage),
+                                         _ptr_array(stage_scales) if stage_scales is not None else None,
+                                         _stream(stream)), "pipesgd_allreduce_direct")
 
 
 class Overlap:

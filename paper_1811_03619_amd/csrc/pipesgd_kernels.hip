@@ -105,7 +105,7 @@ struct BucketTable {
 };
 
 // One launch of a ring kernel.  Worker r (blockIdx.y) handles chunk
-// (r - chunk_rot) mod p, tile slots [slot_base, slot_base + gridDim.x / split).
+// (r - chunk_rot - blockIdx.z) mod p, tile slots [slot_base, slot_base + gridDim.x / split).
 struct RingArgs {
     const float *g[kMaxW];      // local gradients
     const void *in[kMaxW];      // payload worker r receives: the sender's slot, or r's own receive staging
@@ -482,7 +482,8 @@ __global__ __launch_bounds__(G::kThreads) void ring_hop_kernel(RingArgs a, Bucke
     if constexpr (RangeOk<MODE, G>::value) {
         __shared__ float red[G::kWaves];
         const int r = blockIdx.y;
-        const UnitRef t = locate<G>(bt, blockIdx.x + a.slot_base * G::kSplit, mod_p(r - a.chunk_rot, a.p));
+        const UnitRef t = locate<G>(bt, blockIdx.x + a.slot_base * G::kSplit,
+                                    mod_p(r - a.chunk_rot - static_cast<int>(blockIdx.z), a.p));
         if (t.empty) return;
         if (t.full) ring_hop_body<MODE, HAS_IN, G, true>(a, t, r, red);
         else        ring_hop_body<MODE, HAS_IN, G, false>(a, t, r, red);
@@ -563,6 +564,40 @@ __global__ __launch_bounds__(G::kThreads) void ring_fused_kernel(RingArgs a, Buc
         if (t.empty) return;
         if (t.full) ring_fused_body<MODE, G, true>(a, t, c, red);
         else        ring_fused_body<MODE, G, false>(a, t, c, red);
+    }
+}
+
+// Owner-side reduction of the one-exchange ("direct") schedule, blockIdx.y =
+// owner j = chunk j: P = g_j; for d = 1..p-1: P = P + D(in_{(j+d) mod p}); every
+// slot <- C(P).  in_k is what worker k sent: its own compressed copy of chunk j.
+template <int MODE, class G, bool FULL>
+__device__ __forceinline__ void direct_reduce_body(const RingArgs &a, const UnitRef &t, int j, float *red)
+{
+    const int p = a.p;
+    float P[G::kPerThread], x[G::kPerThread];
+    load_f32<G, FULL, kNtGrad>(a.g[j] + t.elem0, t.len, P);
+    for (int d = 1; d < p; ++d) {
+        const int k = mod_p(j + d, p);
+        const float scale_in = MODE == PIPESGD_QUANT8 ? a.in_sc[k][t.elem0 / kTile] : 0.0f;
+        load_payload<MODE, G, FULL, kNtPayIn>(a.in[k], t.elem0, t.len, scale_in, x);
+#pragma unroll
+        for (int i = 0; i < G::kPerThread; ++i) P[i] = P[i] + x[i];
+    }
+    float scale = 0.0f;
+    if constexpr (MODE == PIPESGD_QUANT8) scale = tile_absmax<G>(P, red);
+    for (int r = 0; r < p; ++r) store_payload<MODE, G, FULL, true>(a.out[r], a.out_sc[r], t.elem0, t.len, scale, P);
+}
+
+template <int MODE, class G>
+__global__ __launch_bounds__(G::kThreads) void direct_reduce_kernel(RingArgs a, BucketTable bt)
+{
+    if constexpr (RangeOk<MODE, G>::value) {
+        __shared__ float red[G::kWaves];
+        const int j = blockIdx.y;
+        const UnitRef t = locate<G>(bt, blockIdx.x + a.slot_base * G::kSplit, j);
+        if (t.empty) return;
+        if (t.full) direct_reduce_body<MODE, G, true>(a, t, j, red);
+        else        direct_reduce_body<MODE, G, false>(a, t, j, red);
     }
 }
 
@@ -856,13 +891,13 @@ int prepare_ring(const pipesgd_ring *ring, RingArgs &ra, BucketTable &bt, uint64
     }
 
 template <int MODE, bool HAS_IN>
-int launch_hop(const LaunchConfig &c, const RingArgs &ra, const BucketTable &bt, uint64_t slots, hipStream_t s)
+int launch_hop(const LaunchConfig &c, const RingArgs &ra, const BucketTable &bt, uint64_t slots, int zdim, hipStream_t s)
 {
 #define X(T, Q)                                                                                                  \
     if (c.threads == T && c.quads == Q) {                                                                        \
         static std::atomic<uint32_t> done{0};                                                                    \
         using G = Geo<T, Q>;                                                                                     \
-        return launch(ring_hop_kernel<MODE, HAS_IN, G>, dim3(static_cast<uint32_t>(slots * G::kSplit), ra.p), T, \
+        return launch(ring_hop_kernel<MODE, HAS_IN, G>, dim3(static_cast<uint32_t>(slots * G::kSplit), ra.p, zdim), T, \
                       c.lds_bytes, s, done, ra, bt);                                                             \
     }
     PIPESGD_FOR_EACH_GEO(X)
@@ -897,6 +932,21 @@ int launch_fused(const LaunchConfig &c, const RingArgs &ra, const BucketTable &b
         static std::atomic<uint32_t> done{0};                                                                    \
         using G = Geo<T, Q>;                                                                                     \
         return launch(ring_fused_kernel<MODE, G>, dim3(static_cast<uint32_t>(slots * G::kSplit), ra.p), T,       \
+                      c.lds_bytes, s, done, ra, bt);                                                             \
+    }
+    PIPESGD_FOR_EACH_GEO(X)
+#undef X
+    return PIPESGD_ERR_ARG;
+}
+
+template <int MODE>
+int launch_direct_reduce(const LaunchConfig &c, const RingArgs &ra, const BucketTable &bt, uint64_t slots, hipStream_t s)
+{
+#define X(T, Q)                                                                                                  \
+    if (c.threads == T && c.quads == Q) {                                                                        \
+        static std::atomic<uint32_t> done{0};                                                                    \
+        using G = Geo<T, Q>;                                                                                     \
+        return launch(direct_reduce_kernel<MODE, G>, dim3(static_cast<uint32_t>(slots * G::kSplit), ra.p), T,    \
                       c.lds_bytes, s, done, ra, bt);                                                             \
     }
     PIPESGD_FOR_EACH_GEO(X)
@@ -964,7 +1014,7 @@ int first_send_impl(int mode, RingArgs ra, const BucketTable &bt, uint64_t slots
     if (slots == 0 || (mode == PIPESGD_NONE && ra.p > 1)) return PIPESGD_OK;
     const LaunchConfig c = g_cfg[kFirstSend][mode];
     ra.chunk_rot = 0;
-#define CALL(M) return launch_hop<M, false>(c, ra, bt, slots, s);
+#define CALL(M) return launch_hop<M, false>(c, ra, bt, slots, 1, s);
     PIPESGD_MODE_SWITCH(mode, CALL)
 #undef CALL
     return PIPESGD_ERR_MODE;
@@ -978,7 +1028,7 @@ int rs_impl(int mode, RingArgs ra, const BucketTable &bt, uint64_t slots, int st
     ra.chunk_rot = step + 1;
     if (!staged && mode == PIPESGD_NONE && step == 0)
         for (int r = 0; r < ra.p; ++r) ra.in[r] = ra.g[(r + ra.p - 1) % ra.p];
-#define CALL(M) return launch_hop<M, true>(c, ra, bt, slots, s);
+#define CALL(M) return launch_hop<M, true>(c, ra, bt, slots, 1, s);
     PIPESGD_MODE_SWITCH(mode, CALL)
 #undef CALL
     return PIPESGD_ERR_MODE;
@@ -1102,6 +1152,49 @@ int pipesgd_allreduce_sim(const pipesgd_ring *ring, int schedule, void *stream)
     return rc;
 }
 
+
+// ------------------------------------------------- the one-exchange schedule --
+
+int pipesgd_allreduce_direct(const pipesgd_ring *ring, void *const *stage, float *const *stage_scales, void *stream)
+{
+    RingArgs ra; BucketTable bt; uint64_t slots = 0;
+    int rc = prepare_ring(ring, ra, bt, slots);
+    if (rc != PIPESGD_OK) return rc;
+    const int mode = ring->mode, p = ring->workers;
+    if (slots == 0) return PIPESGD_OK;
+    if (p > 1) {
+        if (!stage || (mode == PIPESGD_QUANT8 && !stage_scales)) return PIPESGD_ERR_ARG;
+        for (int r = 0; r < p; ++r) {
+            if (!stage[r] || (mode == PIPESGD_QUANT8 && !stage_scales[r])) return PIPESGD_ERR_ARG;
+            if (!aligned16(stage[r]) || (mode == PIPESGD_QUANT8 && !aligned16(stage_scales[r]))) return PIPESGD_ERR_ALIGN;
+        }
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (p > 1) {
+        // exchange 1: worker k compresses every chunk it does not own into its send buffer
+        // (chunks k-1, k-2, ..., k-(p-1) along gridDim.z)
+        RingArgs sc = ra;
+        for (int r = 0; r < p; ++r) { sc.out[r] = stage[r]; sc.out_sc[r] = mode == PIPESGD_QUANT8 ? stage_scales[r] : nullptr; }
+        sc.chunk_rot = 1;
+        const LaunchConfig c = g_cfg[kFirstSend][mode];
+#define CALL(M) rc = launch_hop<M, false>(c, sc, bt, slots, p - 1, s);
+        PIPESGD_MODE_SWITCH(mode, CALL)
+#undef CALL
+        if (rc != PIPESGD_OK) return rc;
+    }
+    // owner j sums its own block and what the others sent, compresses once, and
+    // (exchange 2) writes the result into every worker's slot
+    RingArgs rd = ra;
+    for (int r = 0; r < p; ++r) {
+        rd.in[r] = p > 1 ? stage[r] : nullptr;
+        rd.in_sc[r] = (p > 1 && mode == PIPESGD_QUANT8) ? stage_scales[r] : nullptr;
+    }
+    const LaunchConfig c2 = g_cfg[kFused][mode];
+#define CALL(M) return launch_direct_reduce<M>(c2, rd, bt, slots, s);
+    PIPESGD_MODE_SWITCH(mode, CALL)
+#undef CALL
+    return PIPESGD_ERR_MODE;
+}
 
 // ------------------------------------------ pipelining within the AllReduce --
 

@@ -59,6 +59,10 @@ class PipeSgdSim:
         self.updates = [B.UpdateArgs(self.slots[i], self.slot_scales[i] if mode == B.QUANT8 else None,
                                      self.w, self.v if momentum != 0.0 else None)
                         for i in range(nslots)]
+        self.stage = self.stage_scales = None
+        if schedule == B.DIRECT:                       # send buffers of the one-exchange schedule
+            self.stage = [payload_empty(mode, n, dev) for _ in range(workers)]
+            self.stage_scales = [torch.zeros(max(ns, 1), dtype=torch.float32, device=dev)[:ns] for _ in range(workers)]
         self.t = 0
 
     # -- data in / out (host <-> device copies; plumbing) --
@@ -88,7 +92,10 @@ class PipeSgdSim:
     def allreduce(self, stream=None) -> int:
         """Enqueue the AllReduce of the current gradients; returns the slot index."""
         i = (self.t + 1) % len(self.rings)
-        B.allreduce_sim(self.rings[i], B.FUSED if self.schedule == B.ONE_LAUNCH else self.schedule, stream)
+        if self.schedule == B.DIRECT:
+            B.allreduce_direct(self.rings[i], self.stage, self.stage_scales if self.mode == B.QUANT8 else None, stream)
+        else:
+            B.allreduce_sim(self.rings[i], B.FUSED if self.schedule == B.ONE_LAUNCH else self.schedule, stream)
         self._last = i
         return i
 

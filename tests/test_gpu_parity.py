@@ -651,3 +651,79 @@ def test_one_launch_iteration_rejects_aliased_slots():
     with pytest.raises(B.PipeSgdError):
         B.iteration_fused(sim.rings[0], sim.updates[0], 0.01, 0.9)
     sync()
+
+
+# ------------------------------------------------ the one-exchange schedule --
+
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("p,n", [(1, 9000), (2, 4096 * 4), (3, 50001), (4, 3), (4, 4096 * 21 + 77), (5, 12289),
+                                 (8, 300007), (16, 70001)])
+def test_allreduce_direct_equals_oracle(orc, mode, p, n):
+    grads = [special_values(n, 41 * p + r) if n > 100 else W.gaussian(n, 1.0, 3, (0, r, 0, 0)) for r in range(p)]
+    want = orc.allreduce_direct(mode, grads)
+    g_dev, slots, scs = ring_buffers(mode, grads)
+    stage = [pay_buf(mode, n) for _ in range(p)]
+    stage_sc = [dev_zeros(B.num_scales(mode, n), fill=-2.0) for _ in range(p)]
+    ring = B.make_ring(mode, n, g_dev, slots, scs if mode == B.QUANT8 else None)
+    B.allreduce_direct(ring, stage, stage_sc if mode == B.QUANT8 else None)
+    sync()
+    for r in range(p):
+        if mode == B.NONE:
+            assert_fp32_close_then_exact(down(slots[r]), want[r][0], f"sum r={r}")
+        else:
+            assert_bits_equal(down(slots[r], mode), want[r][0], f"payload r={r}")
+        if mode == B.QUANT8:
+            assert_bits_equal(down(scs[r]), want[r][1], f"scales r={r}")
+    if mode == B.NONE and p > 1:          # same order, no codec: the ring gives the same bits
+        ring_res = orc.allreduce(mode, grads)
+        assert_bits_equal(down(slots[0]), ring_res[0][0], "direct vs ring")
+
+
+@pytest.mark.parametrize("mode", [B.TRUNC16, B.QUANT8])
+def test_allreduce_direct_bucketed_and_hand_cases(orc, mode):
+    p = 4
+    specs = W.scaled_config(5, 8)
+    numels = [s.numel for s in specs]
+    buckets, offs, N = B.bucket_plan(numels, 1 << 16)
+    packed = [orc.pack(W.gradient_tensors_for(specs, 5, r, seed=3), offs, N) for r in range(p)]
+    pays = [np.zeros(N, dtype=orc.payload_dtype(mode)) for _ in range(p)]
+    scs_ref = [np.zeros(orc.num_scales(mode, N), np.float32) for _ in range(p)]
+    for (st, nb) in buckets:                      # the oracle per bucket, as for the ring
+        res = orc.allreduce_direct(mode, [g[st:st + nb] for g in packed])
+        for r in range(p):
+            pays[r][st:st + nb] = res[r][0]
+            if mode == B.QUANT8:
+                scs_ref[r][st // 4096: st // 4096 + res[r][1].size] = res[r][1]
+    g_dev = [up(g) for g in packed]
+    slots = [pay_buf(mode, N, poison=False) for _ in range(p)]
+    scs = [dev_zeros(B.num_scales(mode, N)) for _ in range(p)]
+    stage = [pay_buf(mode, N) for _ in range(p)]
+    stage_sc = [dev_zeros(B.num_scales(mode, N)) for _ in range(p)]
+    ring = B.make_ring(mode, N, g_dev, slots, scs if mode == B.QUANT8 else None, buckets)
+    B.allreduce_direct(ring, stage, stage_sc if mode == B.QUANT8 else None)
+    sync()
+    for r in range(p):
+        assert_bits_equal(down(slots[r], mode), pays[r], f"payload r={r}")
+        if mode == B.QUANT8:
+            assert_bits_equal(down(scs[r]), scs_ref[r], f"scales r={r}")
+    # the hand-worked two-worker cases of the oracle's pins
+    ce = 4096
+    g0, g1 = np.zeros(2 * ce, np.float32), np.zeros(2 * ce, np.float32)
+    if mode == B.TRUNC16:
+        g0[0] = g0[ce] = 1.0
+        g1[0] = g1[ce] = -(2.0 ** -8 + 2.0 ** -16)
+    else:
+        for base in (0, ce):
+            g0[base], g0[base + 1] = 127.0, 10.4
+            g1[base], g1[base + 1] = 0.0, 20.4
+    g_dev, slots, scs = ring_buffers(mode, [g0, g1])
+    stage = [pay_buf(mode, 2 * ce) for _ in range(2)]
+    stage_sc = [dev_zeros(2) for _ in range(2)]
+    ring = B.make_ring(mode, 2 * ce, g_dev, slots, scs if mode == B.QUANT8 else None)
+    B.allreduce_direct(ring, stage, stage_sc if mode == B.QUANT8 else None)
+    sync()
+    got = down(slots[1], mode)
+    if mode == B.TRUNC16:
+        assert (got[0], got[ce]) == (0x3F7F, 0x3F7E)
+    else:
+        assert (got[0], got[1], got[ce], got[ce + 1]) == (127, 31, 127, 30)

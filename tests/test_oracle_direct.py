@@ -1,0 +1,127 @@
+"""Pins for the oracle's second AllReduce schedule, the one-exchange "direct"
+schedule (arXiv 1811.03619, Sec. 3.1, closing remark: the analysis carries over
+to other AllReduce algorithms; the result is still the element-wise sum sent to
+all).  Hand arithmetic, direct sums and counts only.
+"""
+import numpy as np
+import pytest
+
+from paper_1811_03619_amd import workloads as W
+
+F = np.float32
+
+
+@pytest.mark.parametrize("mode", [0, 1, 2])
+@pytest.mark.parametrize("p,n", [(2, 10007), (3, 4096 * 3), (4, 4096 * 8 + 9), (4, 5), (5, 30000), (1, 5000)])
+def test_direct_equals_plain_sum_on_exact_inputs(orc, mode, p, n):
+    # integers in [-25, 25]: sums of up to 5 stay below 128, exact under 16-bit truncation.  For the
+    # quantiser every block of every worker additionally carries one 127 (at a position where the
+    # others hold 0), so that every contribution and every sum is quantised with scale 127 (step 1).
+    g = [W.small_integers(n, -25, 25, 61, (p, r, 0, 0)) for r in range(p)]
+    if mode == 2:
+        for blk in range(0, n, 4096):
+            assert min(n, blk + 4096) - blk >= p
+            for r in range(p):
+                for q in range(p):
+                    g[q][blk + r] = 127.0 if q == r else 0.0
+    want = np.sum(np.stack(g).astype(np.float64), axis=0).astype(F)
+    res = orc.allreduce_direct(mode, g)
+    assert len(res) == p
+    for pay, sc in res:
+        assert np.array_equal(orc.decompress(mode, pay, sc), want)
+        if mode == 2:
+            assert np.all(sc == F(127.0))
+    for r in range(1, p):
+        assert np.array_equal(res[r][0], res[0][0])
+
+
+def test_direct_and_ring_agree_bitwise_without_compression(orc):
+    # same summation order (block j: workers j, j+1, ...), so identical bits
+    p, n = 4, 4096 * 5 + 17
+    g = [W.gaussian(n, 0.03, 63, (0, r, 0, 0)) for r in range(p)]
+    a, b = orc.allreduce_direct(orc.NONE, g), orc.allreduce(orc.NONE, g)
+    for r in range(p):
+        assert np.array_equal(a[r][0].view(np.uint32), b[r][0].view(np.uint32))
+
+
+def test_direct_order_starts_at_the_owner(orc):
+    # (2^24, 1, -2^24, 3) summed left to right gives 3; any other start gives 4 or 5
+    p, ce = 4, 4096
+    vals = [2.0 ** 24, 1.0, -2.0 ** 24, 3.0]
+    g = [np.zeros(p * ce, dtype=F) for _ in range(p)]
+    for c in range(p):
+        for j in range(p):
+            g[(c + j) % p][c * ce:(c + 1) * ce] = vals[j]
+    for pay, _ in orc.allreduce_direct(orc.NONE, g):
+        assert np.all(pay == F(3.0))
+
+
+def test_direct_truncates_twice_not_p_times(orc):
+    # owner holds 1 + 2^-8 in full precision, the three others send 2^-8 (exact in
+    # 16 bits): sum 1 + 4*2^-8 = 1.015625 = 0x3F82.  The ring, which truncates the
+    # running sum on every hop, gives 0x3F80 on the same input.
+    p, ce = 4, 4096
+    g = [np.zeros(p * ce, dtype=F) for _ in range(p)]
+    for c in range(p):
+        g[c][c * ce] = 1 + 2.0 ** -8
+        for j in range(1, p):
+            g[(c + j) % p][c * ce] = 2.0 ** -8
+    for pay, _ in orc.allreduce_direct(orc.TRUNC16, g):
+        for c in range(p):
+            assert pay[c * ce] == 0x3F82
+    for pay, _ in orc.allreduce(orc.TRUNC16, g):
+        for c in range(p):
+            assert pay[c * ce] == 0x3F80
+
+
+def test_direct_sender_is_compressed_owner_is_not(orc):
+    # p = 2.  Block 0 (owner 0): 1.0 + D(C(-(2^-8+2^-16))) = 1 - 2^-8 = 0x3F7F.
+    # Block 1 (owner 1): -(2^-8+2^-16) + D(C(1.0)) = 1 - 2^-8 - 2^-16 -> cut to 0x3F7E.
+    ce = 4096
+    g0, g1 = np.zeros(2 * ce, dtype=F), np.zeros(2 * ce, dtype=F)
+    g0[0] = g0[ce] = 1.0
+    g1[0] = g1[ce] = -(2.0 ** -8 + 2.0 ** -16)
+    for pay, _ in orc.allreduce_direct(orc.TRUNC16, [g0, g1]):
+        assert pay[0] == 0x3F7F and pay[ce] == 0x3F7E
+    # quantised: worker 0 has (127, 10.4), worker 1 has (0, 20.4) in both blocks.
+    #  block 0 (owner 0): (127, 10.4) + D(C(0, 20.4)) = (127, ~30.8) -> codes (127, 31)
+    #  block 1 (owner 1): (0, 20.4) + D(C(127, 10.4)) = (0, 20.4) + (127, 10) = (127, 30.4) -> (127, 30)
+    for base in (0, ce):
+        g0[base], g0[base + 1] = 127.0, 10.4
+        g1[base], g1[base + 1] = 0.0, 20.4
+    for q, sc in orc.allreduce_direct(orc.QUANT8, [g0, g1]):
+        assert sc.tolist() == [127.0, 127.0]
+        assert (q[0], q[1], q[ce], q[ce + 1]) == (127, 31, 127, 30)
+
+
+@pytest.mark.parametrize("mode", [1, 2])
+def test_direct_error_bound_is_two_codec_passes(orc, mode):
+    p, n = 4, 4096 * 6 + 1001
+    g = [W.gaussian(n, 1e-3, 65, (mode, r, 0, 0)) for r in range(p)]
+    exact = np.sum(np.stack(g).astype(np.float64), axis=0)
+    res = orc.allreduce_direct(mode, g)
+    out = orc.decompress(mode, *res[0]).astype(np.float64)
+    if mode == 1:
+        sabs = np.sum(np.abs(np.stack(g).astype(np.float64)), axis=0)
+        assert np.all(np.abs(out - exact) <= 2 * 2.0 ** -7 * sabs * (1 + 1e-6))
+        ring = orc.decompress(mode, *orc.allreduce(mode, g)[0]).astype(np.float64)
+        # fewer truncations: smaller error on average than the ring's
+        assert np.mean(np.abs(out - exact)) < np.mean(np.abs(ring - exact))
+    else:
+        for b in range(-(-n // 4096)):
+            sl = slice(b * 4096, min(n, (b + 1) * 4096))
+            smax = sum(float(np.max(np.abs(x[sl]))) for x in g)
+            # each contribution: half a step of its own scale; the sum: half a step of at most smax(1+...)
+            assert np.max(np.abs(out[sl] - exact[sl])) <= 2 * smax / 254.0 * 1.05
+    for r in range(1, p):
+        assert np.array_equal(res[r][0], res[0][0])
+
+
+def test_direct_round_and_volume_counts(orc):
+    # 2 rounds; per worker (p-1)/p n sent in round 1 and (p-1)/p n in round 2 (the ring's volume,
+    # Eq. 5's 2((p-1)/p) n); (p-1)/p n reduced
+    p, n = 4, 4 * 4096 * 6
+    g = [W.gaussian(n, 0.01, 67, (0, r, 0, 0)) for r in range(p)]
+    c = np.zeros(3, dtype=np.uint64)
+    orc.allreduce_direct(orc.TRUNC16, g, c)
+    assert c.tolist() == [2, 2 * (p - 1) * n // p, (p - 1) * n // p]

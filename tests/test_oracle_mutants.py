@@ -14,7 +14,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SRC = os.path.join(ROOT, "oracle", "pipesgd_oracle.c")
 
 PIN_FILES = ["tests/test_oracle_codec.py", "tests/test_oracle_ring.py", "tests/test_oracle_update.py",
-             "tests/test_oracle_bucket.py"]
+             "tests/test_oracle_bucket.py", "tests/test_oracle_direct.py"]
 
 # (name, text to find, replacement)
 MUTANTS = [
@@ -74,6 +74,21 @@ MUTANTS = [
      "if (grad_scale != 1.0f) gi = gi * grad_scale;", ""),
     ("chunks_not_block_aligned",
      "return (per + ORC_QBLOCK - 1) / ORC_QBLOCK * ORC_QBLOCK;", "return per;"),
+    ("direct_adds_in_the_opposite_order",
+     "int k = modp(j + d, p);", "int k = modp(j - d, p);"),
+    ("direct_contributions_travel_uncompressed",
+     "orc_decompress(mode, msg, msg_sc, len, tmp);",
+     "for (size_t i = 0; i < len; ++i) tmp[i] = g_local[k][lo + i];"),
+    ("direct_owner_compresses_its_own_block_too",
+     "for (size_t i = 0; i < len; ++i) P[i] = g_local[j][lo + i];",
+     "for (size_t i = 0; i < len; ++i) P[i] = g_local[j][lo + i]; "
+     "orc_compress(mode, P, len, msg, msg_sc); orc_decompress(mode, msg, msg_sc, len, P);"),
+    ("direct_result_not_compressed_for_the_owner",
+     "for (int r = 0; r < p; ++r) {                   /* round 2: j -> everyone (and its own copy) */",
+     "for (int r = 0; r < p; ++r) { if (r == j && mode == ORC_NONE + 1) { for (size_t i = 0; i < len; ++i) "
+     "((uint16_t *)out_payload[r])[lo + i] = (uint16_t)((f2u(P[i]) + 0x8000u) >> 16); continue; }"),
+    ("direct_reports_one_round",
+     "counters[0] = p > 1 ? 2 : 0;", "counters[0] = p > 1 ? 1 : 0;"),
     ("counters_count_one_direction_only",
      "R->elems_sent[r] += len;\n        R->bytes_sent[r] += nb + 4 * ns;", ""),
 ]
