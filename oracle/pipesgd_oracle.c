@@ -19,7 +19,7 @@
  *   - Algorithm 1, compute thread lines 4-5: decompress the aggregated
  *     gradient of iteration t-K, then w[t] = w[t-1] - gamma * g_sum[t-K].
  *
- * Readings taken where the paper is silent (all listed in the design notes):
+ * Readings taken where the paper is silent:
  *   ring direction r -> r+1; block c starts its sum on worker c; the local
  *   operand of every sum is the worker's full-precision fp32 block; the
  *   send-back rounds forward the compressed block verbatim; truncation keeps
@@ -33,8 +33,12 @@
  * fixes); build with -ffp-contract=off and without fast-math so that every
  * operation written below is exactly one rounding.
  *
+ * A second schedule with the same result definition, the one-exchange
+ * "direct" AllReduce, is at the end of the ring section.
+ *
  * Pinned by tests/test_oracle_*.py (closed forms, invariants, exhaustive
- * codec sweeps, hand-worked tiny cases).  Parity unpinned: nothing exported
+ * codec sweeps, hand-worked tiny cases; tests/test_oracle_mutants.py checks
+ * that planted mistakes trip them).  Parity unpinned: nothing exported
  * here lacks a pin; the *choices* listed above are readings, not facts of the
  * paper.
  */
