@@ -215,6 +215,8 @@ def main() -> int:
 
     if args.phases:
         out["phases_ms"] = time_phases(sim, B, torch, np)
+    if buckets:
+        out["bucketing"] = time_packing(sim, B, torch, np, numels, offs, n)
 
     if args.calib_copy > 0:
         dst = torch.empty_like(sim.g_local[0])
@@ -238,6 +240,42 @@ def main() -> int:
     if study is not None:
         print(json.dumps(study), flush=True)
     return 0
+
+
+def time_packing(sim, B, torch, np, numels, offs, n, reps: int = 20):
+    """Step a0, timed on its own (it is not part of the timed iteration): gather
+    every worker's per-layer gradient tensors into its packed buffer, one launch
+    for all tensors of all workers, and the scatter back."""
+    p, dev = sim.p, sim.device
+    starts = np.cumsum([0] + [ne + (-ne) % 4 for ne in numels])        # 16-byte aligned tensors in one arena
+    arenas = [torch.randn(int(starts[-1]), device=dev) * 1e-3 for _ in range(p)]
+    tptr, pptr, ne = [], [], []
+    for r in range(p):
+        for ti, n_i in enumerate(numels):
+            tptr.append(arenas[r].data_ptr() + 4 * int(starts[ti]))
+            pptr.append(sim.g_local[r].data_ptr() + 4 * offs[ti])
+            ne.append(n_i)
+    tab, total = B.segments_prepare(tptr, pptr, ne)
+    tab_dev = torch.frombuffer(bytearray(bytes(tab)), dtype=torch.uint8).to(dev)
+
+    def timed(fn):
+        ts = []
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        for _ in range(reps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(); fn(); b.record()
+            torch.cuda.synchronize()
+            ts.append(a.elapsed_time(b))
+        return float(np.median(ts))
+
+    pack_ms = timed(lambda: B.pack(tab_dev, len(ne), total))
+    unpack_ms = timed(lambda: B.unpack(tab_dev, len(ne), total))
+    moved = 8.0 * p * float(sum(numels))
+    return {"tensors": len(numels), "workers": p, "launches": 1, "pack_ms": round(pack_ms, 5),
+            "unpack_ms": round(unpack_ms, 5), "pack_GBps": round(moved / pack_ms / 1e6, 1),
+            "unpack_GBps": round(moved / unpack_ms / 1e6, 1)}
 
 
 def committed_traffic(cfg: int, mode_name: str):

@@ -727,3 +727,48 @@ def test_allreduce_direct_bucketed_and_hand_cases(orc, mode):
         assert (got[0], got[ce]) == (0x3F7F, 0x3F7E)
     else:
         assert (got[0], got[1], got[ce], got[ce + 1]) == (127, 31, 127, 30)
+
+
+# ------------------------------------------------------------ random cases --
+
+@pytest.mark.parametrize("case", range(24))
+def test_random_shapes_all_schedules(orc, case):
+    # seeded random worker counts, lengths, bucket layouts and modes; every
+    # AllReduce schedule and the update against the oracle
+    rng = np.random.Generator(np.random.Philox(key=9000 + case))
+    mode = int(rng.integers(0, 3))
+    p = int(rng.choice([1, 2, 3, 4, 5, 6, 7, 8, 11, 16]))
+    if rng.random() < 0.5:
+        numels = [int(x) for x in rng.choice([1, 2, 7, 64, 100, 4095, 4096, 4097, 9000, 33000, 70000],
+                                             size=int(rng.integers(1, 12)))]
+        buckets, offs, n = B.bucket_plan(numels, int(rng.choice([4096, 20000, 65536])))
+        if len(buckets) > B.MAX_BUCKETS:
+            pytest.skip("more buckets than the library takes")
+        tens = [[W.gaussian(ne, 1e-2, 100 + case, (r, ti, 0, 0)) for ti, ne in enumerate(numels)] for r in range(p)]
+        grads = [orc.pack(t, offs, n) for t in tens]
+    else:
+        buckets, n = None, int(rng.integers(1, 200000))
+        grads = [special_values(n, 1000 * case + r) if n > 100 else W.gaussian(n, 1.0, case, (0, r, 0, 0))
+                 for r in range(p)]
+    want = orc.allreduce_bucketed(mode, grads, buckets) if buckets else orc.allreduce(mode, grads)
+    for schedule in (B.STEPWISE, B.FUSED):
+        g_dev, slots, scs = ring_buffers(mode, grads, poison=not buckets)
+        ring = B.make_ring(mode, n, g_dev, slots, scs if mode == B.QUANT8 else None, buckets)
+        B.allreduce_sim(ring, schedule)
+        sync()
+        for r in range(p):
+            assert_bits_equal(down(slots[r], mode), want[r][0], f"payload r={r} schedule={schedule}")
+            if mode == B.QUANT8 and not buckets:
+                assert_bits_equal(down(scs[r]), want[r][1], f"scales r={r}")
+    # update of all replicas from the result
+    lr, m = float(rng.choice([0.01, 0.1])), float(rng.choice([0.0, 0.9]))
+    w0 = [W.gaussian(n, 1.0, 7 + case, (r, 1, 0, 0)) for r in range(p)]
+    v0 = [W.gaussian(n, 0.1, 7 + case, (r, 2, 0, 0)) for r in range(p)]
+    w, v = [up(x) for x in w0], [up(x) for x in v0]
+    args = B.UpdateArgs(slots, scs if mode == B.QUANT8 else None, w, v if m else None)
+    B.apply_update_multi(mode, args, n, lr, m, 1.0)
+    sync()
+    for r in range(p):
+        orc.sgd_update(mode, want[r][0], want[r][1], w0[r], v0[r] if m else None, lr, m, 1.0)
+        assert_fp32_close_then_exact(down(w[r]), w0[r], f"w r={r}")
+        assert_fp32_close_then_exact(down(v[r]), v0[r], f"v r={r}")
