@@ -772,3 +772,41 @@ def test_random_shapes_all_schedules(orc, case):
         orc.sgd_update(mode, want[r][0], want[r][1], w0[r], v0[r] if m else None, lr, m, 1.0)
         assert_fp32_close_then_exact(down(w[r]), w0[r], f"w r={r}")
         assert_fp32_close_then_exact(down(v[r]), v0[r], f"v r={r}")
+
+
+# ------------------------------------------------------- capacity and zeros --
+
+@pytest.mark.parametrize("mode", MODES)
+def test_sixty_four_buckets_and_all_zero_gradients(orc, mode):
+    p = 4
+    numels = [4096 + 17 * i for i in range(64)]                    # one tensor per bucket: the library's maximum
+    buckets, offs, n = B.bucket_plan(numels, 4096)
+    assert len(buckets) == 64
+    grads = [orc.pack([W.gaussian(ne, 1e-3, 3, (r, ti, 0, 0)) for ti, ne in enumerate(numels)], offs, n)
+             for r in range(p)]
+    for ti in (0, 5, 63):                                          # some buckets are all zero on every worker
+        for g in grads:
+            g[offs[ti]:offs[ti] + numels[ti]] = 0.0
+    want = orc.allreduce_bucketed(mode, grads, buckets)
+    for schedule in (B.STEPWISE, B.FUSED):
+        g_dev, slots, scs = ring_buffers(mode, grads, poison=False)
+        ring = B.make_ring(mode, n, g_dev, slots, scs if mode == B.QUANT8 else None, buckets)
+        B.allreduce_sim(ring, schedule)
+        sync()
+        for r in range(p):
+            got = down(slots[r], mode)
+            assert_bits_equal(got, want[r][0], f"payload r={r}")
+            assert not got[offs[5]:offs[5] + numels[5]].any()       # zeros in, zero payload out
+            if mode == B.QUANT8:
+                assert_bits_equal(down(scs[r]), want[r][1], f"scales r={r}")
+                assert down(scs[r])[offs[5] // 4096] == 0.0
+    with pytest.raises(B.PipeSgdError):                             # 65 buckets: refused, nothing launched
+        B.bucket_plan([4096] * 65, 4096)
+    # an all-zero slot leaves the model untouched bit for bit
+    w0 = W.gaussian(n, 1.0, 5)
+    w = up(w0)
+    zero_slot = pay_buf(mode, n, poison=False)
+    zero_sc = dev_zeros(B.num_scales(mode, n))
+    B.apply_update(mode, zero_slot, zero_sc if mode == B.QUANT8 else None, n, w, None, 0.1)
+    sync()
+    assert_bits_equal(down(w), w0, "w after a zero slot")
