@@ -321,12 +321,12 @@ void orc_allreduce(int mode, int p, size_t n, const float *const *g_local,
 
 /* A second AllReduce schedule with the same definition of the result (Sec. 3.1
  * notes that its conclusions carry over to other AllReduce algorithms): every
- * worker is the owner of one block.  Round 1: worker k sends the compressed
+ * worker is the owner of one block.  Exchange 1: worker k sends the compressed
  * block j of its gradient straight to owner j, for every j != k.  The owner
  * starts from its own full-precision block and adds the decompressed
  * contributions in the order of increasing ring distance (j+1, j+2, ...), then
- * compresses once.  Round 2: the owner sends the compressed result to everyone.
- * Two rounds instead of 2(p-1), the same volume, and every value goes through
+ * compresses once.  Exchange 2: the owner sends the compressed result to everyone.
+ * Two exchanges instead of 2(p-1) rounds, the same volume, and every value goes through
  * the codec twice instead of p times.  counters (may be NULL): [0] rounds,
  * [1] elements sent by worker 0, [2] elements reduced by worker 0. */
 void orc_allreduce_direct(int mode, int p, size_t n, const float *const *g_local,
@@ -343,14 +343,14 @@ void orc_allreduce_direct(int mode, int p, size_t n, const float *const *g_local
         for (size_t i = 0; i < len; ++i) P[i] = g_local[j][lo + i];
         for (int d = 1; d < p; ++d) {
             int k = modp(j + d, p);
-            orc_compress(mode, g_local[k] + lo, len, msg, msg_sc);      /* round 1: k -> j */
+            orc_compress(mode, g_local[k] + lo, len, msg, msg_sc);      /* exchange 1: k -> j */
             orc_decompress(mode, msg, msg_sc, len, tmp);
             for (size_t i = 0; i < len; ++i) P[i] = P[i] + tmp[i];
             if (k == 0) sent0 += len;
             if (j == 0) reduced0 += len;
         }
         orc_compress(mode, P, len, msg, msg_sc);
-        for (int r = 0; r < p; ++r) {                   /* round 2: j -> everyone (and its own copy) */
+        for (int r = 0; r < p; ++r) {                   /* exchange 2: j -> everyone (and its own copy) */
             memcpy((char *)out_payload[r] + orc_payload_bytes(mode, lo), msg, orc_payload_bytes(mode, len));
             size_t ns = orc_num_scales(mode, len);
             if (ns) memcpy(out_scales[r] + lo / ORC_QBLOCK, msg_sc, ns * 4);

@@ -118,7 +118,7 @@ def test_direct_error_bound_is_two_codec_passes(orc, mode):
 
 
 def test_direct_round_and_volume_counts(orc):
-    # 2 rounds; per worker (p-1)/p n sent in round 1 and (p-1)/p n in round 2 (the ring's volume,
+    # 2 exchanges; per worker (p-1)/p n sent in the first and (p-1)/p n in the second (the ring's volume,
     # Eq. 5's 2((p-1)/p) n); (p-1)/p n reduced
     p, n = 4, 4 * 4096 * 6
     g = [W.gaussian(n, 0.01, 67, (0, r, 0, 0)) for r in range(p)]

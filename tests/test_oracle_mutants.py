@@ -84,7 +84,7 @@ MUTANTS = [
      "for (size_t i = 0; i < len; ++i) P[i] = g_local[j][lo + i]; "
      "orc_compress(mode, P, len, msg, msg_sc); orc_decompress(mode, msg, msg_sc, len, P);"),
     ("direct_result_not_compressed_for_the_owner",
-     "for (int r = 0; r < p; ++r) {                   /* round 2: j -> everyone (and its own copy) */",
+     "for (int r = 0; r < p; ++r) {                   /* exchange 2: j -> everyone (and its own copy) */",
      "for (int r = 0; r < p; ++r) { if (r == j && mode == ORC_NONE + 1) { for (size_t i = 0; i < len; ++i) "
      "((uint16_t *)out_payload[r])[lo + i] = (uint16_t)((f2u(P[i]) + 0x8000u) >> 16); continue; }"),
     ("direct_reports_one_round",
