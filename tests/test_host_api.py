@@ -190,3 +190,33 @@ def test_timing_models_follow_the_papers_equations():
     # Eq. 7
     assert B.model_scaling_efficiency(1.0, 5.0, 3.0) == 1.0
     assert B.model_scaling_efficiency(1.0, 1.0, 4.0) == 0.5
+
+
+def test_header_is_plain_c_and_links_from_c(tmp_path):
+    # the boundary is a C ABI: the header must compile as C99 and a C program must link and run
+    import subprocess
+    src = tmp_path / "abi.c"
+    src.write_text(r'''
+#include <stdio.h>
+#include "pipesgd.h"
+int main(void) {
+    pipesgd_ring ring;
+    pipesgd_bucket b[4];
+    uint64_t numels[3] = {10, 5000, 3}, offs[3], n_packed = 0;
+    int nb = pipesgd_bucket_plan(numels, 3, 4096, b, 4, offs, &n_packed);
+    ring.workers = 4;
+    printf("%d %llu %llu %llu %s %d\n", nb, (unsigned long long)n_packed,
+           (unsigned long long)pipesgd_chunk_elems(60965224ull, ring.workers),
+           (unsigned long long)pipesgd_payload_bytes(PIPESGD_TRUNC16, 10), pipesgd_strerror(PIPESGD_ERR_MODE),
+           pipesgd_ring_first_send(0, 0));
+    return 0;
+}
+''')
+    exe = tmp_path / "abi"
+    inc = os.path.join(ROOT, "include")
+    libdir = os.path.join(ROOT, "paper_1811_03619_amd")
+    subprocess.check_call(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", inc, str(src),
+                           "-L", libdir, "-lpipesgd", "-Wl,-rpath," + libdir, "-Wl,-rpath,/opt/rocm/lib", "-o", str(exe)])
+    out = subprocess.check_output([str(exe)], text=True).split()
+    # buckets {10}, {5000} (oversized, alone), {3}: starts 0, 4096, 12288 -> packed length 16384
+    assert out[:4] == ["3", "16384", "15245312", "20"] and out[-1] == "-1"
