@@ -727,17 +727,17 @@ __global__ __launch_bounds__(256) void segment_copy_kernel(const pipesgd_segment
     const uint64_t e0 = (tile - s.first_tile) * kTile;
     if (e0 >= s.numel) return;
     const uint64_t rem = s.numel - e0;
-    const uint32_t len = rem < static_cast<uint64_t>(kTile) ? static_cast<uint32_t>(rem) : kTile;
     const float *in = (TO_PACKED ? s.tensor : s.packed) + e0;
     float *out = (TO_PACKED ? s.packed : s.tensor) + e0;
-    const bool vec = len == kTile &&
-        ((reinterpret_cast<uintptr_t>(in) | reinterpret_cast<uintptr_t>(out)) & 15) == 0;
-    if (vec) {
+    const bool whole = rem >= static_cast<uint64_t>(kTile);
+    const bool aligned = ((reinterpret_cast<uintptr_t>(in) | reinterpret_cast<uintptr_t>(out)) & 15) == 0;
+    if (whole && aligned) {
         float x[G::kPerThread];
         load_f32_full<G, true>(in, x);
         store_f32<G, true, false>(out, kTile, x);
     } else {
-        for (uint32_t i = threadIdx.x; i < len; i += 256) out[i] = in[i];
+        // tensors sit at arbitrary 4-byte offsets inside a bucket: element-wise, still coalesced
+        for (uint64_t i = threadIdx.x; i < rem && i < static_cast<uint64_t>(kTile); i += 256) out[i] = in[i];
     }
 }
 
