@@ -312,6 +312,10 @@ def time_phases(sim, B, torch, np, reps: int = 20):
     res["allreduce_stepwise"] = timed(lambda: B.allreduce_sim(ring, B.STEPWISE))
     res["allreduce_fused"] = timed(lambda: B.allreduce_sim(ring, B.FUSED))
     res["update_all_replicas"] = timed(lambda: sim.update_from(1))
+    one = B.UpdateArgs(sim.slots[1][:1], sim.slot_scales[1][:1] if sim.mode == B.QUANT8 else None, sim.w[:1],
+                       sim.v[:1] if sim.momentum != 0.0 else None)
+    res["update_one_replica"] = timed(lambda: B.apply_update_multi(sim.mode, one, sim.n, sim.lr, sim.momentum,
+                                                                   sim.grad_scale))
     return res
 
 
