@@ -537,12 +537,15 @@ template <int MODE, class G, bool FULL>
 __device__ __forceinline__ void ring_fused_body(const RingArgs &a, const UnitRef &t, int c, float (*red)[G::kWaves])
 {
     const int p = a.p;
-    float P[G::kPerThread], g[G::kPerThread];
+    float P[G::kPerThread], g[G::kPerThread], gnext[G::kPerThread];
     load_f32<G, FULL, kNtGrad>(a.g[c] + t.elem0, t.len, P);
+    if (p > 1) load_f32<G, FULL, kNtGrad>(a.g[mod_p(c + 1, p)] + t.elem0, t.len, gnext);
     int flip = 0;
     for (int j = 1; j < p; ++j) {
-        const int wkr = mod_p(c + j, p);
-        load_f32<G, FULL, kNtGrad>(a.g[wkr] + t.elem0, t.len, g);
+#pragma unroll
+        for (int k = 0; k < G::kPerThread; ++k) g[k] = gnext[k];
+        // the next worker's block is requested before this hop's arithmetic
+        if (j + 1 < p) load_f32<G, FULL, kNtGrad>(a.g[mod_p(c + j + 1, p)] + t.elem0, t.len, gnext);
         float scale = 0.0f;
         if constexpr (MODE == PIPESGD_QUANT8) { scale = tile_absmax<G>(P, red[flip]); flip ^= 1; }
         through_the_wire<MODE, G>(P, scale);
@@ -759,7 +762,7 @@ LaunchConfig g_cfg[kNumKinds][3] = {
     /* first send     */ {{256, 4, 0}, {128, 2, 0}, {512, 2, 32768}},
     /* reduce-scatter */ {{128, 2, 0}, {128, 2, 0}, {256, 4, 32768}},
     /* all-gather     */ {{128, 2, 0}, {256, 2, 0}, {256, 1, 0}},
-    /* fused          */ {{256, 4, 0}, {256, 4, 0}, {256, 4, 0}},
+    /* fused          */ {{256, 1, 0}, {256, 1, 0}, {256, 4, 0}},
     /* update         */ {{256, 1, 65536}, {256, 1, 65536}, {256, 1, 0}},
     /* compress       */ {{256, 4, 0}, {256, 4, 0}, {256, 4, 0}},
     /* decompress     */ {{256, 4, 0}, {256, 4, 0}, {256, 4, 0}},
