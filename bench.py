@@ -333,42 +333,57 @@ def study_within_allreduce(sim, B, torch, np, mode, n, n_true, p, reps: int = 15
     recv_sc = [torch.zeros(max(ns, 1), dtype=torch.float32, device=dev)[:ns] for _ in range(p)] if mode == B.QUANT8 else None
     ring = sim.rings[0]
     ov = B.Overlap()
-    wire = torch.cuda.Stream()
+    # the library's two non-blocking streams: they run concurrently (two streams drawn from torch's pool may share
+    # a hardware queue and then serialise), and nothing on them orders itself against the default stream
+    rt = B.Runtime()
+    comp, wire = rt.stream(0), rt.stream(1)
 
     def timed(fn):
-        ts = []
+        import time as _time
         for _ in range(3):
             fn()
+        rt.sync()
         torch.cuda.synchronize()
-        for _ in range(reps):
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record(); fn(); b.record()
-            torch.cuda.synchronize()
-            ts.append(a.elapsed_time(b))
+        ts = []
+        for _ in range(3):
+            t0 = _time.perf_counter()
+            for _ in range(reps):
+                fn()
+            rt.sync()
+            ts.append((_time.perf_counter() - t0) / reps * 1e3)
         return float(np.median(ts))
 
-    res = {"study": "within-allreduce", "unit": "ms"}
-    res["in_place_stepwise"] = round(timed(lambda: B.allreduce_sim(ring, B.STEPWISE)), 5)
-    res["reduce_rounds_in_place"] = round(timed(lambda: [B.ring_reduce_scatter_step(ring, s) for s in range(p - 1)]), 5)
-    res["transfer_rounds_only"] = round(timed(lambda: [B.ring_allgather_step(ring, s) for s in range(p - 1)]), 5)
-    res["sequential_transfer_then_reduce"] = round(
-        timed(lambda: B.allreduce_pipelined(ring, recv, recv_sc, 1, ov, None, None)), 5)
-    res["pipelined_full_speed_transfer"] = {}
-    for seg in (1, 2, 4, 8):
-        res["pipelined_full_speed_transfer"][str(seg)] = round(
-            timed(lambda: B.allreduce_pipelined(ring, recv, recv_sc, seg, ov, None, wire)), 5)
-    # a link slower than the reduction: each worker's transfers carried by k workgroups
-    res["limited_link"] = []
-    for k in (64, 32, 16):
-        seq = timed(lambda: B.allreduce_pipelined(ring, recv, recv_sc, 1, ov, None, None, wire_workgroups=k))
-        row = {"wire_workgroups_per_worker": k, "sequential": round(seq, 5), "pipelined": {}}
-        for seg in (2, 4, 8):
-            row["pipelined"][str(seg)] = round(
-                timed(lambda: B.allreduce_pipelined(ring, recv, recv_sc, seg, ov, None, wire, wire_workgroups=k)), 5)
-        best = min(row["pipelined"].values())
-        row["hidden_ms"] = round(seq - best, 5)
-        row["hidden_fraction_of_reduce_stage"] = round((seq - best) / res["reduce_rounds_in_place"], 4)
-        res["limited_link"].append(row)
+    def pipelined(seg, two_streams, **kw):
+        return timed(lambda: B.allreduce_pipelined(ring, recv, recv_sc, seg, ov, comp, wire if two_streams else comp,
+                                                   **kw))
+
+    res = {"study": "within-allreduce", "unit": "ms", "timing": "wall clock over back-to-back calls"}
+    res["in_place_stepwise"] = round(timed(lambda: B.allreduce_sim(ring, B.STEPWISE, comp)), 5)
+    res["reduce_rounds_in_place"] = round(
+        timed(lambda: [B.ring_reduce_scatter_step(ring, s, comp) for s in range(p - 1)]), 5)
+    res["transfer_rounds_only"] = round(timed(lambda: [B.ring_allgather_step(ring, s, comp) for s in range(p - 1)]), 5)
+    res["sequential_transfer_then_reduce"] = round(pipelined(1, False), 5)
+    res["pipelined_full_speed_transfer"] = {str(seg): round(pipelined(seg, True), 5) for seg in (1, 2, 4, 8)}
+    # a link that is a resource of its own: after each transfer the wire stream idles for the time the bytes
+    # would take on a network of the given speed (per worker); stage 2 overlaps that idle time
+    res["network_link"] = []
+    chunk_mib = B.payload_bytes(mode, B.chunk_elems(n, p)) / 2.0 ** 20
+    for gbps in (200.0, 50.0, 12.5):
+        us_per_mib = 2.0 ** 20 / (gbps * 1e3)              # GB/s -> us per MiB
+        seq = pipelined(1, False, link_us_per_mib=us_per_mib)
+        row = {"link_GBps_per_worker": gbps, "link_ms_per_round": round(chunk_mib * us_per_mib * 1e-3, 4),
+               "sequential": round(seq, 5),
+               "pipelined": {str(seg): round(pipelined(seg, True, link_us_per_mib=us_per_mib), 5)
+                             for seg in (2, 4, 8)}}
+        row["hidden_ms"] = round(seq - min(row["pipelined"].values()), 5)
+        res["network_link"].append(row)
+    # a link made of a few workgroups inside the same HBM (latency-bound, so it slows down under load)
+    res["limited_link_in_hbm"] = []
+    for k in (16,):
+        row = {"wire_workgroups_per_worker": k, "sequential": round(pipelined(1, False, wire_workgroups=k), 5),
+               "pipelined": {str(seg): round(pipelined(seg, True, wire_workgroups=k), 5) for seg in (2, 4)}}
+        res["limited_link_in_hbm"].append(row)
+    rt.close()
     ov.close()
     return res
 

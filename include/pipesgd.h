@@ -202,9 +202,14 @@ void pipesgd_overlap_destroy(pipesgd_overlap *ov);
  * wire_workgroups: 0 = every transfer runs at full memory speed.  k > 0 = each
  * worker's transfers are carried by only k workgroups that walk the sub-block:
  * a link of limited bandwidth that leaves the rest of the GPU to stage 2, which
- * is the situation of the paper (the network is slower than the reduction). */
+ * is the situation of the paper (the network is slower than the reduction).
+ * link_us_per_mib: 0 = none.  x > 0 = before every transfer lands in the staging
+ * buffer the wire stream idles for x microseconds per MiB that one worker sends
+ * in it (one wavefront, no memory traffic): the time the bytes spend on a network
+ * of 1/x MiB/us -- Eq. 5's beta -- which, unlike a copy inside one HBM, competes
+ * with nothing, so stage 2 of the previous sub-block runs beside it. */
 int pipesgd_allreduce_pipelined(const pipesgd_ring *ring, void *const *recv, float *const *recv_scales,
-                                int segments, int wire_workgroups, pipesgd_overlap *ov,
+                                int segments, int wire_workgroups, float link_us_per_mib, pipesgd_overlap *ov,
                                 void *compute_stream, void *wire_stream);
 
 /* ----------------------------------------------------------------- update -- */

@@ -134,7 +134,7 @@ def lib():
     L.pipesgd_overlap_destroy.restype = None
     L.pipesgd_overlap_destroy.argtypes = [vp]
     L.pipesgd_allreduce_pipelined.restype = i32
-    L.pipesgd_allreduce_pipelined.argtypes = [C.POINTER(RingStruct), vp, vp, i32, i32, vp, vp, vp]
+    L.pipesgd_allreduce_pipelined.argtypes = [C.POINTER(RingStruct), vp, vp, i32, i32, f32, vp, vp, vp]
     L.pipesgd_runtime_create.restype = i32
     L.pipesgd_runtime_create.argtypes = [C.POINTER(vp)]
     L.pipesgd_runtime_destroy.restype = None
@@ -296,10 +296,11 @@ class Overlap:
 
 
 def allreduce_pipelined(ring: RingStruct, recv: Sequence, recv_scales: Optional[Sequence], segments: int,
-                        overlap: Overlap, compute_stream=None, wire_stream=None, wire_workgroups: int = 0) -> None:
+                        overlap: Overlap, compute_stream=None, wire_stream=None, wire_workgroups: int = 0,
+                        link_us_per_mib: float = 0.0) -> None:
     check(lib().pipesgd_allreduce_pipelined(C.byref(ring), _ptr_array(recv),
                                             _ptr_array(recv_scales) if recv_scales is not None else None,
-                                            segments, wire_workgroups, overlap.handle,
+                                            segments, wire_workgroups, link_us_per_mib, overlap.handle,
                                             _stream(compute_stream), _stream(wire_stream)),
           "pipesgd_allreduce_pipelined")
 

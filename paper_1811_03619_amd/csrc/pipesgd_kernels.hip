@@ -1229,13 +1229,14 @@ static bool overlap_event(pipesgd_overlap *ov, size_t i, hipEvent_t *e)
 }
 
 int pipesgd_allreduce_pipelined(const pipesgd_ring *ring, void *const *recv, float *const *recv_scales,
-                                int segments, int wire_workgroups, pipesgd_overlap *ov,
+                                int segments, int wire_workgroups, float link_us_per_mib, pipesgd_overlap *ov,
                                 void *compute_stream, void *wire_stream)
 {
     RingArgs ra; BucketTable bt; uint64_t slots = 0;
     int rc = prepare_ring(ring, ra, bt, slots);
     if (rc != PIPESGD_OK) return rc;
-    if (!ov || segments < 1 || wire_workgroups < 0 || ring->num_buckets > 1) return PIPESGD_ERR_ARG;
+    if (!ov || segments < 1 || wire_workgroups < 0 || !(link_us_per_mib >= 0.0f) || ring->num_buckets > 1)
+        return PIPESGD_ERR_ARG;
     const int mode = ring->mode, p = ring->workers;
     if (slots == 0) return PIPESGD_OK;
     if (p > 1) {
@@ -1248,6 +1249,12 @@ int pipesgd_allreduce_pipelined(const pipesgd_ring *ring, void *const *recv, flo
     hipStream_t cs = static_cast<hipStream_t>(compute_stream), ws = static_cast<hipStream_t>(wire_stream);
     const uint64_t S = static_cast<uint64_t>(segments) < slots ? static_cast<uint64_t>(segments) : slots;
     auto seg_lo = [&](uint64_t g) { return slots * g / S; };
+    // time on the link for `tiles` tiles of one worker's payload (all workers' links run in parallel)
+    const double tile_mib = static_cast<double>(pipesgd_payload_bytes(mode, kTile)) / (1024.0 * 1024.0);
+    auto link_delay = [&](uint64_t tiles, hipStream_t st) -> int {
+        if (link_us_per_mib <= 0.0f) return PIPESGD_OK;
+        return pipesgd_synthetic_compute(static_cast<float>(link_us_per_mib * tile_mib * static_cast<double>(tiles)), 1, st);
+    };
 
     // event layout: [0] entry, [1] done, then per segment: sent, and per (round, segment): copied, reduced
     size_t next_event = 0;
@@ -1285,7 +1292,8 @@ int pipesgd_allreduce_pipelined(const pipesgd_ring *ring, void *const *recv, flo
                 w.out_sc[r] = mode == PIPESGD_QUANT8 ? recv_scales[r] : nullptr;
             }
             if (!wait(ws, ready[g])) return PIPESGD_ERR_HIP;
-            rc = copy_impl(mode, w, bt, count, step + 1, static_cast<uint32_t>(wire_workgroups), ws);
+            rc = link_delay(count, ws);               // the payload is under way for this long, then it lands
+            if (rc == PIPESGD_OK) rc = copy_impl(mode, w, bt, count, step + 1, static_cast<uint32_t>(wire_workgroups), ws);
             if (rc != PIPESGD_OK) return rc;
             hipEvent_t copied;
             if (!record(ws, &copied) || !wait(cs, copied)) return PIPESGD_ERR_HIP;
@@ -1305,7 +1313,8 @@ int pipesgd_allreduce_pipelined(const pipesgd_ring *ring, void *const *recv, flo
     hipEvent_t reduced_all;
     if (!record(cs, &reduced_all) || !wait(ws, reduced_all)) return PIPESGD_ERR_HIP;
     for (int step = 0; step <= p - 2; ++step) {
-        rc = copy_impl(mode, ra, bt, slots, step, static_cast<uint32_t>(wire_workgroups), ws);
+        rc = link_delay(slots, ws);
+        if (rc == PIPESGD_OK) rc = copy_impl(mode, ra, bt, slots, step, static_cast<uint32_t>(wire_workgroups), ws);
         if (rc != PIPESGD_OK) return rc;
     }
     hipEvent_t done;

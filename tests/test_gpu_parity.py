@@ -507,7 +507,8 @@ def test_allreduce_pipelined_equals_oracle(orc, mode, p, n, segments, two_stream
             for t in slots:
                 t.fill_(0x33 if mode != B.NONE else 7.0)
         B.allreduce_pipelined(ring, recv, recv_sc if mode == B.QUANT8 else None, segments, ov,
-                              None, wire if two_streams else None, wire_workgroups=(0 if rep == 0 else 3))
+                              None, wire if two_streams else None, wire_workgroups=(0 if rep == 0 else 3),
+                              link_us_per_mib=(0.0 if rep == 0 else 20.0))
         sync()
         for r in range(p):
             if mode == B.NONE:
