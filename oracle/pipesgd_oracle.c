@@ -33,8 +33,9 @@
  * fixes); build with -ffp-contract=off and without fast-math so that every
  * operation written below is exactly one rounding.
  *
- * A second schedule with the same result definition, the one-exchange
- * "direct" AllReduce, is at the end of the ring section.
+ * Two more schedules with the same result definition follow the ring
+ * section: the one-exchange "direct" AllReduce and recursive halving and
+ * doubling.
  *
  * Pinned by tests/test_oracle_*.py (closed forms, invariants, exhaustive
  * codec sweeps, hand-worked tiny cases; tests/test_oracle_mutants.py checks
@@ -359,6 +360,90 @@ void orc_allreduce_direct(int mode, int p, size_t n, const float *const *g_local
     }
     if (counters) { counters[0] = p > 1 ? 2 : 0; counters[1] = sent0; counters[2] = reduced0; }
     free(P); free(tmp); free(msg); free(msg_sc);
+}
+
+/* ------------------------------------- recursive halving and doubling -- */
+
+/* A third AllReduce schedule, one of those Sec. 3.1 names next to the ring
+ * (recursive halving and doubling, after Thakur, Rabenseifner and Gropp,
+ * 2005); p must be a power of two.  Blocks and the codec are the ring's.
+ *
+ * Reduce-scatter by recursive halving, rounds k = 0 .. log2(p)-1, distance
+ * h = p / 2^(k+1): worker r and its partner r XOR h hold partial sums over the
+ * same 2h consecutive blocks (the blocks whose index agrees with r above bit
+ * h).  r keeps the h blocks whose index also agrees with r in bit h and sends
+ * the other h, compressed, to the partner; the partner does the reverse.  Each
+ * adds what it receives, decompressed, to its own full-precision partial sum
+ * (the first round's "partial sum" is the local gradient).  After the last
+ * round worker r holds block r fully reduced and compresses it once.
+ *
+ * All-gather by recursive doubling, distances d = 1, 2, .. p/2: worker r and
+ * r XOR d swap, byte for byte, every compressed block they hold.
+ *
+ * For p = 4, block c:  P = (g_c + D(C(g_{c^2}))) + D(C(g_{c^1} + D(C(g_{c^3})))),
+ * a codec chain of depth log2(p) instead of the ring's p-1.
+ * counters (may be NULL): [0] rounds, [1] elements sent by worker 0,
+ * [2] elements worker 0 received and added. */
+int orc_allreduce_hd(int mode, int p, size_t n, const float *const *g_local,
+                     void *const *out_payload, float *const *out_scales, uint64_t *counters)
+{
+    if (p < 1 || (p & (p - 1)) != 0) return -1;
+    size_t ce = orc_chunk_elems(n, p);
+    size_t pb = orc_payload_bytes(mode, n), ns = orc_num_scales(mode, n);
+    float **acc = (float **)malloc((size_t)p * sizeof(*acc));           /* each worker's partial sums   */
+    char **msg = (char **)malloc((size_t)p * sizeof(*msg));             /* what each worker sends       */
+    float **msg_sc = (float **)malloc((size_t)p * sizeof(*msg_sc));
+    float *tmp = (float *)malloc((n + 1) * sizeof(float));
+    for (int r = 0; r < p; ++r) {
+        acc[r] = (float *)malloc((n + 1) * sizeof(float));
+        memcpy(acc[r], g_local[r], n * sizeof(float));
+        msg[r] = (char *)malloc(pb + 1);
+        msg_sc[r] = (float *)malloc((ns + 1) * sizeof(float));
+    }
+    uint64_t sent0 = 0, reduced0 = 0;
+    int rounds = 0;
+
+    for (int h = p / 2; h >= 1; h /= 2) {               /* halving rounds */
+        for (int r = 0; r < p; ++r) {                   /* everyone sends ... */
+            int keep0 = r & ~(h - 1), send0 = keep0 ^ h;
+            size_t lo = chunk_lo(n, ce, send0), hi = chunk_hi(n, ce, send0 + h - 1);
+            if (hi < lo) hi = lo;
+            orc_compress(mode, acc[r] + lo, hi - lo, msg[r] + orc_payload_bytes(mode, lo), msg_sc[r] + lo / ORC_QBLOCK);
+            if (r == 0) sent0 += hi - lo;
+        }
+        for (int r = 0; r < p; ++r) {                   /* ... then everyone receives and sums */
+            int partner = r ^ h, keep0 = r & ~(h - 1);
+            size_t lo = chunk_lo(n, ce, keep0), hi = chunk_hi(n, ce, keep0 + h - 1);
+            if (hi < lo) hi = lo;
+            orc_decompress(mode, msg[partner] + orc_payload_bytes(mode, lo), msg_sc[partner] + lo / ORC_QBLOCK, hi - lo, tmp);
+            for (size_t i = 0; i < hi - lo; ++i) acc[r][lo + i] = acc[r][lo + i] + tmp[i];
+            if (r == 0) reduced0 += hi - lo;
+        }
+        ++rounds;
+    }
+
+    for (int r = 0; r < p; ++r) {                       /* the owner compresses its block once */
+        size_t lo = chunk_lo(n, ce, r), hi = chunk_hi(n, ce, r);
+        orc_compress(mode, acc[r] + lo, hi - lo, (char *)out_payload[r] + orc_payload_bytes(mode, lo),
+                     ns ? out_scales[r] + lo / ORC_QBLOCK : NULL);
+    }
+    for (int d = 1; d < p; d *= 2) {                    /* doubling rounds: r takes what r XOR d holds */
+        for (int r = 0; r < p; ++r) {
+            int partner = r ^ d, have0 = partner & ~(d - 1);
+            size_t lo = chunk_lo(n, ce, have0), hi = chunk_hi(n, ce, have0 + d - 1);
+            if (hi < lo) hi = lo;
+            memcpy((char *)out_payload[r] + orc_payload_bytes(mode, lo),
+                   (const char *)out_payload[partner] + orc_payload_bytes(mode, lo), orc_payload_bytes(mode, hi - lo));
+            size_t k = orc_num_scales(mode, hi - lo);
+            if (k) memcpy(out_scales[r] + lo / ORC_QBLOCK, out_scales[partner] + lo / ORC_QBLOCK, k * 4);
+            if (partner == 0) sent0 += hi - lo;
+        }
+        ++rounds;
+    }
+    if (counters) { counters[0] = (uint64_t)rounds; counters[1] = sent0; counters[2] = reduced0; }
+    for (int r = 0; r < p; ++r) { free(acc[r]); free(msg[r]); free(msg_sc[r]); }
+    free(acc); free(msg); free(msg_sc); free(tmp);
+    return 0;
 }
 
 /* --------------------------------------------------------------- update -- */

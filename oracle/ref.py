@@ -81,6 +81,8 @@ def lib():
         L.orc_allreduce.argtypes = [i32, i32, sz, vp, vp, vp]
         L.orc_allreduce_direct.restype = None
         L.orc_allreduce_direct.argtypes = [i32, i32, sz, vp, vp, vp, vp]
+        L.orc_allreduce_hd.restype = i32
+        L.orc_allreduce_hd.argtypes = [i32, i32, sz, vp, vp, vp, vp]
         L.orc_sgd_update.restype = None
         L.orc_sgd_update.argtypes = [i32, vp, vp, sz, vp, vp, f32, f32, f32]
         _lib = L
@@ -242,6 +244,21 @@ def allreduce_direct(mode: int, g_local: Sequence[np.ndarray], counters: Optiona
     pays = [np.zeros(n, dtype=_PAYLOAD_DTYPE[mode]) for _ in range(p)]
     scs = [np.zeros(num_scales(mode, n), dtype=np.float32) if mode == QUANT8 else None for _ in range(p)]
     lib().orc_allreduce_direct(mode, p, n, _ptr_array(g), _ptr_array(pays), _ptr_array(scs), _ptr(counters))
+    return list(zip(pays, scs))
+
+
+def allreduce_hd(mode: int, g_local: Sequence[np.ndarray], counters: Optional[np.ndarray] = None):
+    """Recursive halving (reduce-scatter) and doubling (all-gather); the number
+    of workers must be a power of two.  Same return shape as ``allreduce``.
+    ``counters``: optional uint64[3] (rounds, elements sent by worker 0,
+    elements worker 0 received and added)."""
+    g = [_f32(x).ravel() for x in g_local]
+    p, n = len(g), g[0].size
+    pays = [np.zeros(n, dtype=_PAYLOAD_DTYPE[mode]) for _ in range(p)]
+    scs = [np.zeros(num_scales(mode, n), dtype=np.float32) if mode == QUANT8 else None for _ in range(p)]
+    rc = lib().orc_allreduce_hd(mode, p, n, _ptr_array(g), _ptr_array(pays), _ptr_array(scs), _ptr(counters))
+    if rc != 0:
+        raise ValueError("recursive halving-doubling needs a power-of-two number of workers")
     return list(zip(pays, scs))
 
 

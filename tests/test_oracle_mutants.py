@@ -14,7 +14,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SRC = os.path.join(ROOT, "oracle", "pipesgd_oracle.c")
 
 PIN_FILES = ["tests/test_oracle_codec.py", "tests/test_oracle_ring.py", "tests/test_oracle_update.py",
-             "tests/test_oracle_bucket.py", "tests/test_oracle_direct.py"]
+             "tests/test_oracle_bucket.py", "tests/test_oracle_direct.py", "tests/test_oracle_hd.py"]
 
 # (name, text to find, replacement)
 MUTANTS = [
@@ -74,6 +74,28 @@ MUTANTS = [
      "if (grad_scale != 1.0f) gi = gi * grad_scale;", ""),
     ("chunks_not_block_aligned",
      "return (per + ORC_QBLOCK - 1) / ORC_QBLOCK * ORC_QBLOCK;", "return per;"),
+    ("hd_halving_distances_ascend",
+     "for (int h = p / 2; h >= 1; h /= 2) {               /* halving rounds */",
+     "for (int h = 1; h < p; h *= 2) {               /* halving rounds */"),
+    ("hd_keeps_the_half_it_should_send",
+     "int partner = r ^ h, keep0 = r & ~(h - 1);", "int partner = r ^ h, keep0 = (r & ~(h - 1)) ^ h;"),
+    ("hd_receiver_truncates_its_own_partial_sum",
+     "for (size_t i = 0; i < hi - lo; ++i) acc[r][lo + i] = acc[r][lo + i] + tmp[i];",
+     "for (size_t i = 0; i < hi - lo; ++i) { volatile uint16_t hh = trunc16_c(acc[r][lo + i]); "
+     "acc[r][lo + i] = (mode == ORC_TRUNC16 ? trunc16_d(hh) : acc[r][lo + i]) + tmp[i]; }"),
+    ("hd_partial_sums_travel_uncompressed",
+     "for (size_t i = 0; i < hi - lo; ++i) acc[r][lo + i] = acc[r][lo + i] + tmp[i];",
+     "for (size_t i = 0; i < hi - lo; ++i) acc[r][lo + i] = acc[r][lo + i] + acc[partner][lo + i];"),
+    ("hd_pairs_neighbours_first",
+     "int partner = r ^ h, keep0 = r & ~(h - 1);",
+     "int partner = r ^ (p / 2 / h), keep0 = r & ~(h - 1);"),
+    ("hd_doubling_takes_the_wrong_blocks",
+     "int partner = r ^ d, have0 = partner & ~(d - 1);", "int partner = r ^ d, have0 = r & ~(d - 1);"),
+    ("hd_reports_the_ring_round_count",
+     "if (counters) { counters[0] = (uint64_t)rounds; counters[1] = sent0; counters[2] = reduced0; }\n    for (int r = 0; r < p; ++r) { free(acc[r]);",
+     "if (counters) { counters[0] = (uint64_t)(2 * (p - 1)); counters[1] = sent0; counters[2] = reduced0; }\n    for (int r = 0; r < p; ++r) { free(acc[r]);"),
+    ("hd_volume_counts_the_halving_only",
+     "if (partner == 0) sent0 += hi - lo;", ""),
     ("direct_adds_in_the_opposite_order",
      "int k = modp(j + d, p);", "int k = modp(j - d, p);"),
     ("direct_contributions_travel_uncompressed",
