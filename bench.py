@@ -32,7 +32,8 @@ def payload_bytes_per_elem(mode: int) -> float:
     return {0: 4.0, 1: 2.0, 2: 1.0 + 4.0 / 4096.0}[mode]
 
 
-def bytes_model(mode: int, n: int, p: int, momentum: bool, fused: bool = False, direct: bool = False):
+def bytes_model(mode: int, n: int, p: int, momentum: bool, fused: bool = False, direct: bool = False,
+                halving_doubling: bool = False):
     """Algorithmic bytes of one iteration, by phase.  Stepwise schedule: every
     hop's payload is written once and read once.  Fused schedule: each gradient
     is read once and each worker's result written once (hop payloads never
@@ -46,6 +47,21 @@ def bytes_model(mode: int, n: int, p: int, momentum: bool, fused: bool = False, 
         reduce_bcast = (4.0 + (p - 1) * cb + p * cb) * n
         return {"direct_scatter": scatter, "direct_reduce_broadcast": reduce_bcast, "update": upd,
                 "total": scatter + reduce_bcast + upd}
+    if halving_doubling:
+        # first message: read the half given away, write it compressed.  Halving round h (= chunks kept per
+        # worker): read own fp32 + the partner's payload over h chunks, write fp32 for the h/2 chunks kept
+        # next and payload for the h/2 sent next (the last round writes one chunk of payload).  Doubling
+        # round d: copy d chunks of payload.  All of it for p workers; a chunk is n/p elements.
+        ce = n / p
+        first = 0.0 if mode == 0 else p * (p // 2) * ce * (4.0 + cb)
+        halving, h = 0.0, p // 2
+        while h >= 1:
+            out = cb if h == 1 else (4.0 + cb) / 2.0
+            halving += p * h * ce * (4.0 + cb + out)
+            h //= 2
+        doubling = (p - 1) * n * 2.0 * cb
+        return {"first_message": first, "halving": halving, "doubling": doubling, "update": upd,
+                "total": first + halving + doubling + upd}
     if fused:
         ar = (4.0 * p + cb * p) * n
         return {"allreduce_fused": ar, "update": upd, "total": ar + upd}
@@ -63,7 +79,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=3, help="workload 1..5 (3 = AlexNet-shaped, 61M, the headline)")
     ap.add_argument("--mode", type=int, default=None, help="override compression mode 0/1/2")
-    ap.add_argument("--schedule", choices=["stepwise", "fused", "one-launch", "direct"], default="stepwise",
+    ap.add_argument("--schedule", choices=["stepwise", "fused", "one-launch", "direct", "halving-doubling"],
+                    default="stepwise",
                     help="stepwise: one launch per ring round, every hop payload in memory (the headline); fused: the "
                          "AllReduce in one launch; one-launch: AllReduce and update of an iteration in one launch")
     ap.add_argument("--workers", type=int, default=4)
@@ -102,7 +119,8 @@ def main() -> int:
     cfg, p = args.config, args.workers
     mode = MODE_OF_CONFIG[cfg] if args.mode is None else args.mode
     momentum = (0.0 if cfg == 1 else 0.9) if args.momentum is None else args.momentum
-    schedule = {"stepwise": B.STEPWISE, "fused": B.FUSED, "one-launch": B.ONE_LAUNCH, "direct": B.DIRECT}[args.schedule]
+    schedule = {"stepwise": B.STEPWISE, "fused": B.FUSED, "one-launch": B.ONE_LAUNCH, "direct": B.DIRECT,
+                "halving-doubling": B.HALVING_DOUBLING}[args.schedule]
 
     specs = W.config_tensors(cfg)
     numels = [s.numel for s in specs]
@@ -174,7 +192,8 @@ def main() -> int:
     gpu_ms_per_step = start_ev.elapsed_time(stop_ev) / args.steps
 
     n_true = int(sum(numels))          # bucket padding is processed but is not part of the model
-    model = bytes_model(mode, n_true, p, momentum != 0.0, fused=(schedule in (B.FUSED, B.ONE_LAUNCH)), direct=(schedule == B.DIRECT))
+    model = bytes_model(mode, n_true, p, momentum != 0.0, fused=(schedule in (B.FUSED, B.ONE_LAUNCH)), direct=(schedule == B.DIRECT),
+                        halving_doubling=(schedule == B.HALVING_DOUBLING))
     value = model["total"] / (ms_per_step * 1e-3) / 1e9
     upd_gbs = model["update"] / (upd_ms * 1e-3) / 1e9 if upd_ms else None
 
@@ -311,6 +330,8 @@ def time_phases(sim, B, torch, np, reps: int = 20):
     res["allgather_step"] = [timed(lambda s=s: B.ring_allgather_step(ring, s)) for s in range(p - 1)]
     res["allreduce_stepwise"] = timed(lambda: B.allreduce_sim(ring, B.STEPWISE))
     res["allreduce_fused"] = timed(lambda: B.allreduce_sim(ring, B.FUSED))
+    if sim.schedule in (B.DIRECT, B.HALVING_DOUBLING):
+        res["allreduce_selected_schedule"] = timed(lambda: sim.allreduce())
     res["update_all_replicas"] = timed(lambda: sim.update_from(1))
     one = B.UpdateArgs(sim.slots[1][:1], sim.slot_scales[1][:1] if sim.mode == B.QUANT8 else None, sim.w[:1],
                        sim.v[:1] if sim.momentum != 0.0 else None)

@@ -175,6 +175,31 @@ int pipesgd_allreduce_sim(const pipesgd_ring *ring, int schedule, void *stream);
 int pipesgd_allreduce_direct(const pipesgd_ring *ring, void *const *stage, float *const *stage_scales,
                              void *stream);
 
+/* A third AllReduce schedule: recursive halving and doubling, one of the
+ * algorithms Sec. 3.1's closing remark names beside the ring (reduce-scatter by
+ * recursive halving, all-gather by recursive doubling, as published by Thakur,
+ * Rabenseifner and Gropp, 2005).  ring->workers must be a power of two
+ * (otherwise PIPESGD_ERR_ARG).  Chunks and codecs are the ring's.
+ *   halving round with distance h = p/2, p/4, .., 1: worker r and partner r^h
+ *   hold partial sums over the same 2h chunks; r keeps the h chunks whose index
+ *   agrees with r in bit h, sends the other h compressed (into stage[r]) and
+ *   computes  P = own + D(stage[r^h])  on the ones it keeps, own = the local
+ *   gradient in the first round and the fp32 partial sum afterwards.  After the
+ *   last round worker r holds chunk r and writes C(P) into its result slot.
+ *   doubling round with distance d = 1, 2, .., p/2: r copies, byte for byte,
+ *   the d chunks r^d holds.
+ * For p = 4, chunk c:  P = (g_c + D(C(g_{c^2}))) + D(C(g_{c^1} + D(C(g_{c^3})))):
+ * a codec chain of depth log2(p) (the ring's is p-1) and 2 log2(p) rounds.
+ * 1 + log2(p) + log2(p) launches (one less without compression): a halving
+ * round also compresses, in the same pass, the part of its sums that is sent
+ * in the next round.
+ * stage / stage_scales: HOST arrays of p DEVICE send buffers, each as large as
+ * a result slot.  partial: HOST array of p DEVICE float buffers of ring->n
+ * elements (the partial sums; needed when p > 2, may be NULL otherwise).
+ * Contents of all three are scratch.  Buckets are supported. */
+int pipesgd_allreduce_halving_doubling(const pipesgd_ring *ring, void *const *stage, float *const *stage_scales,
+                                       float *const *partial, void *stream);
+
 /* ---------------------------------------- pipelining within the AllReduce -- */
 
 /* Host-side resources (HIP events) of the two-stream schedule below.  No device

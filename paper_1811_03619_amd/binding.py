@@ -17,6 +17,7 @@ NONE, TRUNC16, QUANT8 = 0, 1, 2
 STEPWISE, FUSED = 0, 1
 ONE_LAUNCH = 2          # pipeline.PipeSgdSim only: pipesgd_iteration_fused
 DIRECT = 3              # pipeline.PipeSgdSim only: pipesgd_allreduce_direct
+HALVING_DOUBLING = 4    # pipeline.PipeSgdSim only: pipesgd_allreduce_halving_doubling
 MAX_WORKERS = 16
 MAX_BUCKETS = 64
 QBLOCK = 4096
@@ -33,6 +34,7 @@ EXPORTS = [
     "pipesgd_runtime_stream", "pipesgd_synthetic_compute",
     "pipesgd_model_sync_time", "pipesgd_model_pipe_ideal_time", "pipesgd_model_pipe_time",
     "pipesgd_model_ring_comm_time", "pipesgd_model_scaling_efficiency", "pipesgd_iteration_fused", "pipesgd_allreduce_direct",
+    "pipesgd_allreduce_halving_doubling",
 ]
 K_FIRST_SEND, K_REDUCE_SCATTER, K_ALLGATHER, K_FUSED, K_UPDATE, K_COMPRESS, K_DECOMPRESS = range(7)
 
@@ -156,6 +158,8 @@ def lib():
     L.pipesgd_model_ring_comm_time.argtypes = [i32, dbl, dbl, dbl, dbl, dbl, i32]
     L.pipesgd_allreduce_direct.restype = i32
     L.pipesgd_allreduce_direct.argtypes = [C.POINTER(RingStruct), vp, vp, vp]
+    L.pipesgd_allreduce_halving_doubling.restype = i32
+    L.pipesgd_allreduce_halving_doubling.argtypes = [C.POINTER(RingStruct), vp, vp, vp, vp]
     L.pipesgd_iteration_fused.restype = i32
     L.pipesgd_iteration_fused.argtypes = [C.POINTER(RingStruct), vp, vp, vp, vp, f32, f32, f32, vp]
     L.pipesgd_set_launch_config.restype = i32
@@ -273,6 +277,15 @@ def allreduce_direct(ring: RingStruct, stage: Sequence, stage_scales: Optional[S
     check(lib().pipesgd_allreduce_direct(C.byref(ring), _ptr_array(stage),
                                          _ptr_array(stage_scales) if stage_scales is not None else None,
                                          _stream(stream)), "pipesgd_allreduce_direct")
+
+
+def allreduce_halving_doubling(ring: RingStruct, stage: Sequence, stage_scales: Optional[Sequence],
+                               partial: Optional[Sequence], stream=None) -> None:
+    check(lib().pipesgd_allreduce_halving_doubling(C.byref(ring), _ptr_array(stage) if stage is not None else None,
+                                                   _ptr_array(stage_scales) if stage_scales is not None else None,
+                                                   _ptr_array(partial) if partial is not None else None,
+                                                   _stream(stream)),
+          "pipesgd_allreduce_halving_doubling")
 
 
 class Overlap:

@@ -490,11 +490,34 @@ __global__ __launch_bounds__(G::kThreads) void ring_hop_kernel(RingArgs a, Bucke
     }
 }
 
+// Byte copy of one unit of payload (and, for a tile's first unit, its scale).
+// Geometry counts 16-byte vectors here: a workgroup copies THREADS*QUADS of them.
+template <int MODE, class G>
+__device__ __forceinline__ void copy_unit(const void *in_pay, const float *in_sc, void *out_pay, float *out_sc, const UnitRef &t)
+{
+    using C = Codec<MODE>;
+    const char *in = static_cast<const char *>(in_pay) + t.elem0 * C::kBytes;
+    char *out = static_cast<char *>(out_pay) + t.elem0 * C::kBytes;
+    if (t.full) {
+        const u32x4 *vi = reinterpret_cast<const u32x4 *>(in);
+        u32x4 *vo = reinterpret_cast<u32x4 *>(out);
+        u32x4 tmp[G::kQuads];
+#pragma unroll
+        for (int i = 0; i < G::kQuads; ++i) tmp[i] = ld<kNtPayIn>(vi + i * G::kThreads + threadIdx.x);
+#pragma unroll
+        for (int i = 0; i < G::kQuads; ++i) st<kNtPayOut>(vo + i * G::kThreads + threadIdx.x, tmp[i]);
+    } else {
+        const uint32_t bytes = t.len * C::kBytes;
+        for (uint32_t i = threadIdx.x; i < bytes; i += G::kThreads) out[i] = in[i];
+    }
+    if (MODE == PIPESGD_QUANT8 && threadIdx.x == 0 && t.elem0 % kTile == 0)
+        out_sc[t.elem0 / kTile] = in_sc[t.elem0 / kTile];
+}
+
 // Payload transfer for every worker: byte copy of one chunk's payload (and
 // scales) from in_r to out_r.  Used for the send-back rounds (in = the
 // neighbour's slot, out = the worker's own slot) and as the "wire" stage of the
-// pipelined schedule (out = the worker's receive staging).  Geometry counts
-// 16-byte vectors here: a workgroup copies THREADS*QUADS of them.
+// pipelined schedule (out = the worker's receive staging).
 template <int MODE, class G>
 __global__ __launch_bounds__(G::kThreads) void ring_copy_kernel(RingArgs a, BucketTable bt)
 {
@@ -511,22 +534,7 @@ __global__ __launch_bounds__(G::kThreads) void ring_copy_kernel(RingArgs a, Buck
         for (uint32_t u = blockIdx.x; u < a.units; u += gridDim.x) {
             const UnitRef t = locate<UnitOnly<kUnitElems>>(bt, u + a.slot_base * kSplit, chunk);
             if (t.empty) continue;
-            const char *in = static_cast<const char *>(a.in[r]) + t.elem0 * C::kBytes;
-            char *out = static_cast<char *>(a.out[r]) + t.elem0 * C::kBytes;
-            if (t.full) {
-                const u32x4 *vi = reinterpret_cast<const u32x4 *>(in);
-                u32x4 *vo = reinterpret_cast<u32x4 *>(out);
-                u32x4 tmp[G::kQuads];
-#pragma unroll
-                for (int i = 0; i < G::kQuads; ++i) tmp[i] = ld<kNtPayIn>(vi + i * G::kThreads + threadIdx.x);
-#pragma unroll
-                for (int i = 0; i < G::kQuads; ++i) st<kNtPayOut>(vo + i * G::kThreads + threadIdx.x, tmp[i]);
-            } else {
-                const uint32_t bytes = t.len * C::kBytes;
-                for (uint32_t i = threadIdx.x; i < bytes; i += G::kThreads) out[i] = in[i];
-            }
-            if (MODE == PIPESGD_QUANT8 && threadIdx.x == 0 && t.elem0 % kTile == 0)
-                a.out_sc[r][t.elem0 / kTile] = a.in_sc[r][t.elem0 / kTile];
+            copy_unit<MODE, G>(a.in[r], a.in_sc[r], a.out[r], a.out_sc[r], t);
         }
     }
 }
@@ -601,6 +609,87 @@ __global__ __launch_bounds__(G::kThreads) void direct_reduce_kernel(RingArgs a, 
         if (t.empty) return;
         if (t.full) direct_reduce_body<MODE, G, true>(a, t, j, red);
         else        direct_reduce_body<MODE, G, false>(a, t, j, red);
+    }
+}
+
+// ---- recursive halving and doubling (Sec. 3.1 names it beside the ring) ----
+// One launch for every worker (blockIdx.y = r).  The worker handles `half`
+// consecutive chunks (blockIdx.z): those starting at r with the bits below
+// `half` cleared (the chunks it keeps in this round), or that start XOR `flip`.
+struct HdArgs {
+    const float *src[kMaxW];    // fp32 operand: the local gradient, later the worker's partial sums
+    const void *in[kMaxW];      // what the worker receives: the partner's send buffer (or slot, when doubling)
+    const float *in_sc[kMaxW];
+    void *pay[kMaxW];           // payload written: the worker's send buffer, or its result slot
+    float *pay_sc[kMaxW];
+    float *acc[kMaxW];          // partial sums the worker keeps in fp32
+    int half;
+    int flip;
+    int next_half;              // kHdReduce: chunks that differ from r in this bit are sent next, so they leave as payload
+};
+enum { kHdSend = 0, kHdReduce = 1, kHdLast = 2 };
+
+__device__ __forceinline__ int hd_chunk(const HdArgs &a, int r)
+{
+    return ((r & ~(a.half - 1)) ^ a.flip) + static_cast<int>(blockIdx.z);
+}
+
+//   kHdSend  : C(src_r)                -> pay_r            (first round's message)
+//   kHdReduce: P = src_r + D(in_r);  P -> acc_r  for the chunks kept next round,
+//                                  C(P) -> pay_r  for the chunks sent next round
+//   kHdLast  : C(src_r + D(in_r))      -> pay_r            (the worker's own block, fully reduced)
+template <int MODE, int STAGE, class G, bool FULL>
+__device__ __forceinline__ void hd_body(const HdArgs &a, const UnitRef &t, int r, bool as_payload, float *red)
+{
+    float P[G::kPerThread];
+    float x[G::kPerThread];
+    if (STAGE != kHdSend) {
+        const float scale_in = MODE == PIPESGD_QUANT8 ? a.in_sc[r][t.elem0 / kTile] : 0.0f;
+        load_payload<MODE, G, FULL, kNtPayIn>(a.in[r], t.elem0, t.len, scale_in, x);
+    }
+    load_f32<G, FULL, kNtGrad>(a.src[r] + t.elem0, t.len, P);
+    if (STAGE != kHdSend) {
+#pragma unroll
+        for (int k = 0; k < G::kPerThread; ++k) P[k] = P[k] + x[k];
+    }
+    if (as_payload) {                                   // uniform over the workgroup
+        float scale = 0.0f;
+        if constexpr (MODE == PIPESGD_QUANT8) scale = tile_absmax<G>(P, red);
+        store_payload<MODE, G, FULL, kNtPayOut>(a.pay[r], a.pay_sc[r], t.elem0, t.len, scale, P);
+    } else {
+        store_f32<G, FULL, false>(a.acc[r] + t.elem0, t.len, P);
+    }
+}
+
+template <int MODE, int STAGE, class G>
+__global__ __launch_bounds__(G::kThreads) void hd_kernel(HdArgs a, BucketTable bt)
+{
+    if constexpr (RangeOk<MODE, G>::value) {
+        __shared__ float red[G::kWaves];
+        const int r = blockIdx.y;
+        const int chunk = hd_chunk(a, r);
+        const UnitRef t = locate<G>(bt, blockIdx.x, chunk);
+        if (t.empty) return;
+        const bool as_payload = STAGE != kHdReduce || ((chunk ^ r) & a.next_half) != 0;
+        if (t.full) hd_body<MODE, STAGE, G, true>(a, t, r, as_payload, red);
+        else        hd_body<MODE, STAGE, G, false>(a, t, r, as_payload, red);
+    }
+}
+
+// Doubling round: worker r copies, byte for byte, the `half` chunks its partner holds.
+template <int MODE, class G>
+__global__ __launch_bounds__(G::kThreads) void hd_copy_kernel(HdArgs a, BucketTable bt)
+{
+    using C = Codec<MODE>;
+    constexpr int kTileVecs = kTile * C::kBytes / 16;
+    constexpr int kUnitVecs = G::kThreads * G::kQuads;
+    if constexpr (kUnitVecs <= kTileVecs) {
+        constexpr int kSplit = kTileVecs / kUnitVecs;
+        constexpr int kUnitElems = kTile / kSplit;
+        const int r = blockIdx.y;
+        const UnitRef t = locate<UnitOnly<kUnitElems>>(bt, blockIdx.x, hd_chunk(a, r));
+        if (t.empty) return;
+        copy_unit<MODE, G>(a.in[r], a.in_sc[r], a.pay[r], a.pay_sc[r], t);
     }
 }
 
@@ -1008,6 +1097,39 @@ int launch_update(const LaunchConfig &c, const UpdateArgs &ua, int replicas, hip
     return PIPESGD_ERR_ARG;
 }
 
+template <int MODE, int STAGE>
+int launch_hd(const LaunchConfig &c, const HdArgs &ha, const BucketTable &bt, uint64_t slots, int p, hipStream_t s)
+{
+#define X(T, Q)                                                                                                  \
+    if (c.threads == T && c.quads == Q) {                                                                        \
+        static std::atomic<uint32_t> done{0};                                                                    \
+        using G = Geo<T, Q>;                                                                                     \
+        return launch(hd_kernel<MODE, STAGE, G>, dim3(static_cast<uint32_t>(slots * G::kSplit), p, ha.half), T,  \
+                      c.lds_bytes, s, done, ha, bt);                                                             \
+    }
+    PIPESGD_FOR_EACH_GEO(X)
+#undef X
+    return PIPESGD_ERR_ARG;
+}
+
+template <int MODE>
+int launch_hd_copy(const LaunchConfig &c, const HdArgs &ha, const BucketTable &bt, uint64_t slots, int p, hipStream_t s)
+{
+    constexpr int kTileVecs = kTile * Codec<MODE>::kBytes / 16;
+#define X(T, Q)                                                                                                  \
+    if (c.threads == T && c.quads == Q) {                                                                        \
+        if constexpr (T * Q <= kTileVecs) {                                                                      \
+            static std::atomic<uint32_t> done{0};                                                                \
+            constexpr int kSplit = kTileVecs / (T * Q);                                                          \
+            return launch(hd_copy_kernel<MODE, Geo<T, Q>>, dim3(static_cast<uint32_t>(slots * kSplit), p, ha.half), T, \
+                          c.lds_bytes, s, done, ha, bt);                                                         \
+        }                                                                                                        \
+    }
+    PIPESGD_FOR_EACH_GEO(X)
+#undef X
+    return PIPESGD_ERR_ARG;
+}
+
 // The four launches below work on tile slots [ra.slot_base, ra.slot_base + slots)
 // of every bucket-chunk; the plain entry points pass the whole range.
 
@@ -1197,6 +1319,92 @@ int pipesgd_allreduce_direct(const pipesgd_ring *ring, void *const *stage, float
     PIPESGD_MODE_SWITCH(mode, CALL)
 #undef CALL
     return PIPESGD_ERR_MODE;
+}
+
+// ------------------------------------------ recursive halving and doubling --
+
+int pipesgd_allreduce_halving_doubling(const pipesgd_ring *ring, void *const *stage, float *const *stage_scales,
+                                       float *const *partial, void *stream)
+{
+    RingArgs ra; BucketTable bt; uint64_t slots = 0;
+    int rc = prepare_ring(ring, ra, bt, slots);
+    if (rc != PIPESGD_OK) return rc;
+    const int mode = ring->mode, p = ring->workers;
+    if ((p & (p - 1)) != 0) return PIPESGD_ERR_ARG;
+    if (slots == 0) return PIPESGD_OK;
+    const bool q8 = mode == PIPESGD_QUANT8;
+    if (p > 1) {
+        if (!stage || (q8 && !stage_scales) || (p > 2 && !partial)) return PIPESGD_ERR_ARG;
+        for (int r = 0; r < p; ++r) {
+            if (!stage[r] || (q8 && !stage_scales[r]) || (p > 2 && !partial[r])) return PIPESGD_ERR_ARG;
+            if (!aligned16(stage[r]) || (q8 && !aligned16(stage_scales[r])) || (p > 2 && !aligned16(partial[r])))
+                return PIPESGD_ERR_ALIGN;
+        }
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    HdArgs ha;
+    for (int r = 0; r < kMaxW; ++r) {
+        ha.src[r] = nullptr; ha.in[r] = nullptr; ha.in_sc[r] = nullptr; ha.pay[r] = nullptr; ha.pay_sc[r] = nullptr;
+        ha.acc[r] = nullptr;
+    }
+    ha.half = 1; ha.flip = 0; ha.next_half = 0;
+    const LaunchConfig c_send = g_cfg[kFirstSend][mode], c_red = g_cfg[kReduceScatter][mode], c_copy = g_cfg[kAllGather][mode];
+
+    if (p == 1) {                                        // nothing to exchange: the slot is C(g)
+        ha.src[0] = ra.g[0]; ha.pay[0] = ra.out[0]; ha.pay_sc[0] = ra.out_sc[0];
+#define CALL(M) return launch_hd<M, kHdSend>(c_send, ha, bt, slots, p, s);
+        PIPESGD_MODE_SWITCH(mode, CALL)
+#undef CALL
+    }
+
+    // first message: every worker compresses the half it gives away (uncompressed
+    // payloads are read from the partner's gradient in place instead)
+    if (mode != PIPESGD_NONE) {
+        for (int r = 0; r < p; ++r) { ha.src[r] = ra.g[r]; ha.pay[r] = stage[r]; ha.pay_sc[r] = q8 ? stage_scales[r] : nullptr; }
+        ha.half = p / 2; ha.flip = p / 2;
+#define CALL(M) rc = launch_hd<M, kHdSend>(c_send, ha, bt, slots, p, s);
+        PIPESGD_MODE_SWITCH(mode, CALL)
+#undef CALL
+        if (rc != PIPESGD_OK) return rc;
+    }
+    // halving rounds: receive, sum, and in the same pass compress what goes out next
+    for (int h = p / 2; h >= 1; h /= 2) {
+        const bool first = h == p / 2, last = h == 1;
+        for (int r = 0; r < p; ++r) {
+            const int partner = r ^ h;
+            ha.src[r] = first ? ra.g[r] : partial[r];
+            ha.in[r] = (first && mode == PIPESGD_NONE) ? static_cast<const void *>(ra.g[partner]) : stage[partner];
+            ha.in_sc[r] = q8 ? stage_scales[partner] : nullptr;
+            ha.pay[r] = last ? ra.out[r] : stage[r];
+            ha.pay_sc[r] = last ? ra.out_sc[r] : (q8 ? stage_scales[r] : nullptr);
+            ha.acc[r] = last ? nullptr : partial[r];
+        }
+        ha.half = h; ha.flip = 0; ha.next_half = h / 2;
+        if (last) {
+#define CALL(M) rc = launch_hd<M, kHdLast>(c_red, ha, bt, slots, p, s);
+            PIPESGD_MODE_SWITCH(mode, CALL)
+#undef CALL
+        } else {
+#define CALL(M) rc = launch_hd<M, kHdReduce>(c_red, ha, bt, slots, p, s);
+            PIPESGD_MODE_SWITCH(mode, CALL)
+#undef CALL
+        }
+        if (rc != PIPESGD_OK) return rc;
+    }
+    // doubling rounds: swap everything held so far with the partner at distance d
+    for (int d = 1; d < p; d *= 2) {
+        for (int r = 0; r < p; ++r) {
+            const int partner = r ^ d;
+            ha.in[r] = ra.out[partner]; ha.in_sc[r] = ra.out_sc[partner];
+            ha.pay[r] = ra.out[r]; ha.pay_sc[r] = ra.out_sc[r];
+        }
+        ha.half = d; ha.flip = d; ha.next_half = 0;
+#define CALL(M) rc = launch_hd_copy<M>(c_copy, ha, bt, slots, p, s);
+        PIPESGD_MODE_SWITCH(mode, CALL)
+#undef CALL
+        if (rc != PIPESGD_OK) return rc;
+    }
+    return PIPESGD_OK;
 }
 
 // ------------------------------------------ pipelining within the AllReduce --

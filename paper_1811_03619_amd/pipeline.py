@@ -59,10 +59,12 @@ class PipeSgdSim:
         self.updates = [B.UpdateArgs(self.slots[i], self.slot_scales[i] if mode == B.QUANT8 else None,
                                      self.w, self.v if momentum != 0.0 else None)
                         for i in range(nslots)]
-        self.stage = self.stage_scales = None
-        if schedule == B.DIRECT:                       # send buffers of the one-exchange schedule
+        self.stage = self.stage_scales = self.partial = None
+        if schedule in (B.DIRECT, B.HALVING_DOUBLING):  # send buffers of the one-exchange / halving-doubling schedules
             self.stage = [payload_empty(mode, n, dev) for _ in range(workers)]
             self.stage_scales = [torch.zeros(max(ns, 1), dtype=torch.float32, device=dev)[:ns] for _ in range(workers)]
+        if schedule == B.HALVING_DOUBLING and workers > 2:      # fp32 partial sums between halving rounds
+            self.partial = [torch.zeros(max(n, 1), dtype=torch.float32, device=dev)[:n] for _ in range(workers)]
         self.t = 0
 
     # -- data in / out (host <-> device copies; plumbing) --
@@ -94,6 +96,9 @@ class PipeSgdSim:
         i = (self.t + 1) % len(self.rings)
         if self.schedule == B.DIRECT:
             B.allreduce_direct(self.rings[i], self.stage, self.stage_scales if self.mode == B.QUANT8 else None, stream)
+        elif self.schedule == B.HALVING_DOUBLING:
+            B.allreduce_halving_doubling(self.rings[i], self.stage,
+                                         self.stage_scales if self.mode == B.QUANT8 else None, self.partial, stream)
         else:
             B.allreduce_sim(self.rings[i], B.FUSED if self.schedule == B.ONE_LAUNCH else self.schedule, stream)
         self._last = i

@@ -730,6 +730,136 @@ def test_allreduce_direct_bucketed_and_hand_cases(orc, mode):
         assert (got[0], got[1], got[ce], got[ce + 1]) == (127, 31, 127, 30)
 
 
+# ------------------------------------------- recursive halving and doubling --
+
+def hd_buffers(mode, n, p, poison=True):
+    stage = [pay_buf(mode, n, poison=poison) for _ in range(p)]
+    stage_sc = [dev_zeros(B.num_scales(mode, n), fill=-2.0) for _ in range(p)]
+    partial = [dev_zeros(n, fill=float("nan") if poison else None) for _ in range(p)] if p > 2 else None
+    return stage, (stage_sc if mode == B.QUANT8 else None), partial
+
+
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("p,n", [(1, 9000), (2, 4096 * 4), (2, 50001), (4, 3), (4, 4096 * 21 + 77), (4, 4096 * 2 + 5),
+                                 (8, 300007), (8, 4096 * 5), (16, 70001), (16, 4096 * 40 + 1)])
+def test_allreduce_halving_doubling_equals_oracle(orc, mode, p, n):
+    grads = [special_values(n, 43 * p + r) if n > 100 else W.gaussian(n, 1.0, 5, (0, r, 0, 0)) for r in range(p)]
+    want = orc.allreduce_hd(mode, grads)
+    g_dev, slots, scs = ring_buffers(mode, grads)
+    stage, stage_sc, partial = hd_buffers(mode, n, p)
+    ring = B.make_ring(mode, n, g_dev, slots, scs if mode == B.QUANT8 else None)
+    for _ in range(2):                 # a second call on used scratch buffers gives the same result
+        B.allreduce_halving_doubling(ring, stage, stage_sc, partial)
+        sync()
+        for r in range(p):
+            if mode == B.NONE:
+                assert_fp32_close_then_exact(down(slots[r]), want[r][0], f"sum r={r}")
+            else:
+                assert_bits_equal(down(slots[r], mode), want[r][0], f"payload r={r}")
+            if mode == B.QUANT8:
+                assert_bits_equal(down(scs[r]), want[r][1], f"scales r={r}")
+    for r in range(p):                 # the inputs are never modified
+        assert_bits_equal(down(g_dev[r]), grads[r], f"gradient r={r}")
+
+
+@pytest.mark.parametrize("mode", [B.TRUNC16, B.QUANT8])
+def test_allreduce_halving_doubling_bucketed_and_hand_cases(orc, mode):
+    p = 4
+    specs = W.scaled_config(5, 8)
+    numels = [s.numel for s in specs]
+    buckets, offs, N = B.bucket_plan(numels, 1 << 16)
+    packed = [orc.pack(W.gradient_tensors_for(specs, 5, r, seed=4), offs, N) for r in range(p)]
+    pays = [np.zeros(N, dtype=orc.payload_dtype(mode)) for _ in range(p)]
+    scs_ref = [np.zeros(orc.num_scales(mode, N), np.float32) for _ in range(p)]
+    for (st, nb) in buckets:                      # the oracle per bucket, as for the ring
+        res = orc.allreduce_hd(mode, [g[st:st + nb] for g in packed])
+        for r in range(p):
+            pays[r][st:st + nb] = res[r][0]
+            if mode == B.QUANT8:
+                scs_ref[r][st // 4096: st // 4096 + res[r][1].size] = res[r][1]
+    g_dev = [up(g) for g in packed]
+    slots = [pay_buf(mode, N, poison=False) for _ in range(p)]
+    scs = [dev_zeros(B.num_scales(mode, N)) for _ in range(p)]
+    stage, stage_sc, partial = hd_buffers(mode, N, p, poison=False)
+    ring = B.make_ring(mode, N, g_dev, slots, scs if mode == B.QUANT8 else None, buckets)
+    B.allreduce_halving_doubling(ring, stage, stage_sc, partial)
+    sync()
+    for r in range(p):
+        assert_bits_equal(down(slots[r], mode), pays[r], f"payload r={r}")
+        if mode == B.QUANT8:
+            assert_bits_equal(down(scs[r]), scs_ref[r], f"scales r={r}")
+    # the hand-worked four-worker cases of the oracle's pins: roles (c, c^2, c^1, c^3) in chunk c
+    ce = 4096
+    g = [np.zeros(p * ce, np.float32) for _ in range(p)]
+    if mode == B.TRUNC16:
+        vals = {0: 1 + 2.0 ** -8, 2: 0.0, 1: 1 + 2.0 ** -7, 3: 2.0 ** -8}
+        for c in range(p):
+            for d, x in vals.items():
+                g[c ^ d][c * ce:(c + 1) * ce] = x
+    else:
+        vals = {0: 10.3, 2: 20.4, 1: 5.3, 3: 7.4}
+        for c in range(p):
+            for r in range(p):
+                g[r][c * ce + r] = 127.0
+            for d, x in vals.items():
+                g[c ^ d][c * ce + 8] = x
+    g_dev, slots, scs = ring_buffers(mode, g)
+    stage, stage_sc, partial = hd_buffers(mode, p * ce, p)
+    ring = B.make_ring(mode, p * ce, g_dev, slots, scs if mode == B.QUANT8 else None)
+    B.allreduce_halving_doubling(ring, stage, stage_sc, partial)
+    sync()
+    for r in range(p):
+        got = down(slots[r], mode)
+        if mode == B.TRUNC16:
+            assert np.all(got == 0x4000)
+        else:
+            assert [int(got[c * ce + 8]) for c in range(p)] == [42] * p
+            assert down(scs[r]).tolist() == [127.0] * p
+
+
+def test_allreduce_halving_doubling_rejects_bad_arguments():
+    n = 4096 * 3
+    for p in (3, 6):
+        sim = PipeSgdSim(B.TRUNC16, p, n, 0.01, 0.9)
+        stage, stage_sc, partial = hd_buffers(B.TRUNC16, n, p)
+        partial = partial or [dev_zeros(n) for _ in range(p)]
+        with pytest.raises(B.PipeSgdError):
+            B.allreduce_halving_doubling(sim.rings[0], stage, None, partial)
+    sim = PipeSgdSim(B.QUANT8, 4, n, 0.01, 0.9)
+    stage, stage_sc, partial = hd_buffers(B.QUANT8, n, 4)
+    with pytest.raises(B.PipeSgdError):
+        B.allreduce_halving_doubling(sim.rings[0], stage, None, partial)          # scales of the send buffers missing
+    with pytest.raises(B.PipeSgdError):
+        B.allreduce_halving_doubling(sim.rings[0], stage, stage_sc, None)         # partial sums missing at p > 2
+    with pytest.raises(B.PipeSgdError):
+        B.allreduce_halving_doubling(sim.rings[0], None, stage_sc, partial)
+    sync()
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_pipe_sgd_run_with_halving_doubling(orc, mode):
+    # five pipelined iterations (width 2) with the halving-doubling AllReduce against
+    # the oracle's schedule-specific AllReduce followed by the oracle's update
+    p, n, lr, m, iters = 4, 4096 * 9 + 321, 0.05, 0.9, 5
+    sim = PipeSgdSim(mode, p, n, lr, m, schedule=B.HALVING_DOUBLING)
+    w0 = W.gaussian(n, 1.0, 21, (0, 0, 0, 0))
+    sim.set_model(w0)
+    w_ref, v_ref = w0.copy(), np.zeros(n, np.float32)
+    stale = None
+    for t in range(1, iters + 1):
+        grads = [W.gaussian(n, 1e-2, 23, (mode, r, t, 0)) for r in range(p)]
+        sim.set_gradients(grads)
+        sim.iteration()
+        sync()
+        fresh = orc.allreduce_hd(mode, grads)
+        if stale is not None:
+            orc.sgd_update(mode, stale[0][0], stale[0][1], w_ref, v_ref, lr, m, 1.0)
+        stale = fresh
+        for r in range(p):
+            assert_fp32_close_then_exact(sim.model(r), w_ref, f"w t={t} r={r}")
+            assert_fp32_close_then_exact(sim.velocity(r), v_ref, f"v t={t} r={r}")
+
+
 # ------------------------------------------------------------ random cases --
 
 @pytest.mark.parametrize("case", range(24))
@@ -761,6 +891,24 @@ def test_random_shapes_all_schedules(orc, case):
             assert_bits_equal(down(slots[r], mode), want[r][0], f"payload r={r} schedule={schedule}")
             if mode == B.QUANT8 and not buckets:
                 assert_bits_equal(down(scs[r]), want[r][1], f"scales r={r}")
+    if p & (p - 1) == 0:
+        if buckets:
+            want_hd = [[np.zeros(n, dtype=orc.payload_dtype(mode)), None] for _ in range(p)]
+            for (st, nb) in buckets:
+                res = orc.allreduce_hd(mode, [g[st:st + nb] for g in grads])
+                for r in range(p):
+                    want_hd[r][0][st:st + nb] = res[r][0]
+        else:
+            want_hd = orc.allreduce_hd(mode, grads)
+        g_dev2, slots2, scs2 = ring_buffers(mode, grads, poison=not buckets)
+        stage, stage_sc, partial = hd_buffers(mode, n, p, poison=not buckets)
+        ring2 = B.make_ring(mode, n, g_dev2, slots2, scs2 if mode == B.QUANT8 else None, buckets)
+        B.allreduce_halving_doubling(ring2, stage, stage_sc, partial)
+        sync()
+        for r in range(p):
+            assert_bits_equal(down(slots2[r], mode), want_hd[r][0], f"payload r={r} halving-doubling")
+            if mode == B.QUANT8 and not buckets:
+                assert_bits_equal(down(scs2[r]), want_hd[r][1], f"scales r={r} halving-doubling")
     # update of all replicas from the result
     lr, m = float(rng.choice([0.01, 0.1])), float(rng.choice([0.0, 0.9]))
     w0 = [W.gaussian(n, 1.0, 7 + case, (r, 1, 0, 0)) for r in range(p)]
