@@ -34,6 +34,24 @@ def full_config_inputs(cfg, p, seed):
     return buckets, n, grads
 
 
+def oracle_allreduce(orc, schedule, mode, grads, buckets):
+    fn = {B.DIRECT: orc.allreduce_direct, B.HALVING_DOUBLING: orc.allreduce_hd}.get(schedule)
+    if fn is None:                                  # the ring: stepwise and fused give the same bits
+        return orc.allreduce_bucketed(mode, grads, buckets) if buckets else orc.allreduce(mode, grads)
+    if not buckets:
+        return fn(mode, grads)
+    n, p = grads[0].size, len(grads)               # every bucket is reduced as a vector of its own
+    out = [(np.zeros(n, dtype=orc.payload_dtype(mode)),
+            np.zeros(orc.num_scales(mode, n), np.float32) if mode == B.QUANT8 else None) for _ in range(p)]
+    for (st, nb) in buckets:
+        res = fn(mode, [g[st:st + nb] for g in grads])
+        for r in range(p):
+            out[r][0][st:st + nb] = res[r][0]
+            if mode == B.QUANT8:
+                out[r][1][st // 4096: st // 4096 + res[r][1].size] = res[r][1]
+    return out
+
+
 @pytest.mark.parametrize("cfg,mode,schedule", [
     (3, B.TRUNC16, B.STEPWISE),     # the headline configuration
     (3, B.TRUNC16, B.FUSED),
@@ -41,6 +59,10 @@ def full_config_inputs(cfg, p, seed):
     (5, B.NONE, B.STEPWISE),
     (5, B.TRUNC16, B.STEPWISE),
     (5, B.TRUNC16, B.FUSED),
+    (3, B.TRUNC16, B.DIRECT),       # the other schedules, each against its own oracle branch
+    (3, B.TRUNC16, B.HALVING_DOUBLING),
+    (5, B.TRUNC16, B.HALVING_DOUBLING),
+    (4, B.QUANT8, B.DIRECT),
 ])
 def test_full_size_two_iterations(orc, cfg, mode, schedule):
     p, lr, m = 4, 0.01, 0.9
@@ -57,7 +79,7 @@ def test_full_size_two_iterations(orc, cfg, mode, schedule):
     sync()
 
     t0 = time.time()
-    A = orc.allreduce_bucketed(mode, grads, buckets) if buckets else orc.allreduce(mode, grads)
+    A = oracle_allreduce(orc, schedule, mode, grads, buckets)
     w_ref, v_ref = w0.copy(), np.zeros(n, np.float32)
     orc.sgd_update(mode, A[0][0], A[0][1], w_ref, v_ref, lr, m, 1.0)     # the t=2 update (t=1's is a no-op)
     print(f"[cfg{cfg}] oracle in {time.time() - t0:.1f}s", flush=True)
