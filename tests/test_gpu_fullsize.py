@@ -103,3 +103,76 @@ def test_full_size_two_iterations(orc, cfg, mode, schedule):
         assert torch.equal(sim.w[r], sim.w[0]) and torch.equal(sim.v[r], sim.v[0]), r
     for r in range(p):
         assert torch.equal(sim.g_local[r].cpu(), torch.from_numpy(grads[r])), "gradients must not be modified"
+
+
+@pytest.mark.parametrize("mode", [B.TRUNC16, B.QUANT8])
+def test_buffers_beyond_4_gib_sampled_tiles(orc, mode):
+    """Largest size exercised: n > 2^31 elements per worker, so fp32 byte offsets pass 2^33 and 16-bit payload
+    offsets pass 2^32.  The oracle would need minutes for the whole vector; chunks and quantisation blocks
+    never interact, so a sampled tile's result depends only on the p workers' values in that tile and on the
+    chunk it lies in -- the oracle computes it from a p-tile vector holding the tile at that chunk position."""
+    p, lr, m = 2, 0.01, 0.9
+    n = (1 << 31) + 4096 * 3 + 100
+    ce = B.chunk_elems(n, p)
+    dev = "cuda:0"
+
+    def pattern(seed, length, sigma):
+        return W.gaussian(length, sigma, seed, (77, 0, 0, 0))
+
+    def tiled(pat):                                       # value at global index i is pat[i % len(pat)]
+        t = torch.from_numpy(pat).to(dev)
+        reps = -(-n // pat.size)
+        return t.repeat(reps)[:n]
+
+    def sample(pat, e0, ln):
+        idx = (e0 + np.arange(ln, dtype=np.int64)) % pat.size
+        return pat[idx]
+
+    g_pat = [pattern(900 + r, 1000003 + 2 * r, 0.01) for r in range(p)]
+    w_pat, v_pat = pattern(910, 999983, 0.05), pattern(911, 1000033, 0.001)
+    g_dev = [tiled(x) for x in g_pat]
+    w = [tiled(w_pat) for _ in range(p)]
+    v = [tiled(v_pat) for _ in range(p)]
+    slots = [torch.zeros(n, dtype={B.TRUNC16: torch.int16, B.QUANT8: torch.int8}[mode], device=dev) for _ in range(p)]
+    ns = B.num_scales(mode, n)
+    scs = [torch.zeros(max(ns, 1), dtype=torch.float32, device=dev)[:ns] for _ in range(p)]
+    print(f"[beyond 4 GiB, mode {mode}] n={n} chunk={ce} buffers ready", flush=True)
+
+    ring = B.make_ring(mode, n, g_dev, slots, scs if mode == B.QUANT8 else None)
+    B.allreduce_sim(ring, B.STEPWISE)
+    B.apply_update_multi(mode, B.UpdateArgs(slots, scs if mode == B.QUANT8 else None, w, v), n, lr, m, 1.0)
+    sync()
+    print("[beyond 4 GiB] device work done", flush=True)
+
+    last_tile = (n - 1) // 4096
+    tiles = sorted({0, 1, (1 << 30) // 4096 - 1, (1 << 30) // 4096, ce // 4096 - 1, ce // 4096, ce // 4096 + 1,
+                    (1 << 31) // 4096 - 1, (1 << 31) // 4096, last_tile - 1, last_tile,
+                    (3 << 29) // 4096, 123457, 400001})
+    for T in tiles:
+        e0 = T * 4096
+        ln = min(4096, n - e0)
+        c = e0 // ce
+        assert (e0 - c * ce) % 4096 == 0
+        small = []
+        for r in range(p):                                # the tile at the start of chunk c of a p-tile vector
+            x = np.zeros(c * 4096 + ln if c == p - 1 else p * 4096, dtype=np.float32)
+            x[c * 4096:c * 4096 + ln] = sample(g_pat[r], e0, ln)
+            small.append(x)
+        assert B.chunk_elems(small[0].size, p) == 4096
+        res = orc.allreduce(mode, small)
+        want_pay = res[0][0][c * 4096:c * 4096 + ln]
+        w_ref, v_ref = sample(w_pat, e0, ln).copy(), sample(v_pat, e0, ln).copy()
+        orc.sgd_update(mode, want_pay, res[0][1][c:c + 1] if mode == B.QUANT8 else None, w_ref, v_ref, lr, m, 1.0)
+        for r in range(p):
+            got = slots[r][e0:e0 + ln].cpu().numpy()
+            assert_bits_equal(got.view(np.uint16) if mode == B.TRUNC16 else got, want_pay, f"payload tile {T} r={r}")
+            if mode == B.QUANT8:
+                assert_bits_equal(scs[r][T:T + 1].cpu().numpy(), res[0][1][c:c + 1], f"scale tile {T} r={r}")
+            assert_fp32_close_then_exact(w[r][e0:e0 + ln].cpu().numpy(), w_ref, f"w tile {T} r={r}")
+            assert_fp32_close_then_exact(v[r][e0:e0 + ln].cpu().numpy(), v_ref, f"v tile {T} r={r}")
+    # properties that hold at any size: replicas identical, gradients untouched, nothing written past the end
+    assert torch.equal(slots[0], slots[1]) and torch.equal(w[0], w[1]) and torch.equal(v[0], v[1])
+    for r in range(p):
+        assert torch.equal(g_dev[r][-5000:].cpu(), torch.from_numpy(sample(g_pat[r], n - 5000, 5000)))
+    del g_dev, w, v, slots, scs
+    torch.cuda.empty_cache()
