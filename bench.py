@@ -92,7 +92,7 @@ def main() -> int:
     ap.add_argument("--graph", action="store_true",
                     help="replay the iterations from a captured HIP graph (two iterations per replay); "
                          "the update kernel is then not bracketed by events, so roofline.achieved is null")
-    ap.add_argument("--study", choices=["within-allreduce", "two-thread-runtime"], default=None,
+    ap.add_argument("--study", choices=["within-allreduce", "two-thread-runtime", "ring-cost-model"], default=None,
                     help="extra measurement printed as its own JSON line after the main one")
     ap.add_argument("--calib-copy", type=int, default=0,
                     help="after the timed region, launch this many plain copies of one worker's gradient "
@@ -252,6 +252,9 @@ def main() -> int:
     if args.study == "two-thread-runtime":
         study = study_two_thread_runtime(sim, B, torch, np, schedule)
 
+    if args.study == "ring-cost-model":
+        study = study_ring_cost_model(B, torch, np, mode, n, p, args.seed)
+
     if args.cpu_seconds > 0:
         out["cpu_baseline"] = cpu_baseline(mode, grads, w0, p, args.lr, momentum, buckets, model["total"],
                                            args.cpu_seconds)
@@ -406,6 +409,59 @@ def study_within_allreduce(sim, B, torch, np, mode, n, n_true, p, reps: int = 15
         res["limited_link_in_hbm"].append(row)
     rt.close()
     ov.close()
+    return res
+
+
+def study_ring_cost_model(B, torch, np, mode, n, p, seed, reps: int = 30):
+    """Eq. 5 as a calculator: alpha (per-round latency) is measured on a vector of
+    one tile per chunk, beta (per byte sent) on the send-back rounds and gamma
+    (per byte reduced) on the transmit-and-reduce rounds of the workload's size;
+    the 2(p-1) rounds of other sizes are then predicted and measured."""
+    from paper_1811_03619_amd.pipeline import PipeSgdSim
+
+    def rounds_ms(m):
+        sim = PipeSgdSim(mode, p, m, 0.01, 0.9)
+        for r in range(p):
+            sim.g_local[r].normal_(0.0, 1e-3, generator=torch.Generator(device=sim.device).manual_seed(seed + r))
+        ring = sim.rings[0]
+        B.ring_first_send(ring)
+
+        def timed(fn):
+            for _ in range(3):
+                fn()
+            ts = []
+            for _ in range(reps):
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record(); fn(); b.record()
+                torch.cuda.synchronize()
+                ts.append(a.elapsed_time(b))
+            return float(np.median(ts))
+
+        rs = timed(lambda: [B.ring_reduce_scatter_step(ring, k) for k in range(p - 1)]) / (p - 1)
+        ag = timed(lambda: [B.ring_allgather_step(ring, k) for k in range(p - 1)]) / (p - 1)
+        both = timed(lambda: ([B.ring_reduce_scatter_step(ring, k) for k in range(p - 1)],
+                              [B.ring_allgather_step(ring, k) for k in range(p - 1)]))
+        del sim
+        torch.cuda.empty_cache()
+        return rs, ag, both
+
+    cb = payload_bytes_per_elem(mode)
+    rs0, ag0, _ = rounds_ms(p * 4096)                      # one tile per chunk: latency only
+    alpha = 0.5 * (rs0 + ag0)
+    rs1, ag1, both1 = rounds_ms(n)
+    wire_bytes = cb * n                                    # Eq. 5's n: bytes of one worker's (compressed) gradient
+    beta = (ag1 - alpha) / (wire_bytes / p)                # ms per byte sent by one worker in one round
+    gamma = (rs1 - alpha) / (wire_bytes / p) - beta        # ms per byte reduced
+    res = {"study": "ring-cost-model", "unit": "ms", "alpha_ms_per_round": round(alpha, 5),
+           "beta_ms_per_MB": round(beta * 1e6, 6), "gamma_ms_per_MB": round(gamma * 1e6, 6),
+           "fitted_on_elements": n, "measured_fit_size": round(both1, 5),
+           "eq5_fit_size": round(B.model_ring_comm_time(p, wire_bytes, alpha, beta, gamma), 5), "predictions": []}
+    for m in (n // 64, n // 16, n // 4, n // 2, 2 * n):
+        m = max(p * 4096, m // 4096 * 4096)
+        _, _, meas = rounds_ms(m)
+        pred = B.model_ring_comm_time(p, cb * m, alpha, beta, gamma)
+        res["predictions"].append({"elements": m, "eq5": round(pred, 5), "measured": round(meas, 5),
+                                   "measured_over_eq5": round(meas / pred, 4)})
     return res
 
 
