@@ -131,6 +131,30 @@ def test_ring_validation_errors():
     assert L.pipesgd_ring_first_send(C.byref(fake_ring(n=0, g=0, pay=0, sc=0)), None) == 0
 
 
+def test_extra_schedules_validate_before_launching():
+    # every call below is rejected (or is a no-op) on the host: nothing is enqueued
+    L = B.lib()
+    arr = lambda vals: (C.c_void_p * len(vals))(*vals)
+    hd = L.pipesgd_allreduce_halving_doubling
+    good = arr([0x40000] * 4)
+    assert hd(None, good, good, good, None) == -1
+    for p in (3, 5, 6, 12):                                 # worker count must be a power of two
+        assert hd(C.byref(fake_ring(p=p)), arr([0x40000] * p), None, arr([0x50000] * p), None) == -1
+    assert hd(C.byref(fake_ring()), None, None, good, None) == -1                     # no send buffers
+    assert hd(C.byref(fake_ring()), good, None, None, None) == -1                     # p > 2 needs partial sums
+    assert hd(C.byref(fake_ring()), arr([0x40000, 0, 0x40000, 0x40000]), None, good, None) == -1
+    assert hd(C.byref(fake_ring()), arr([0x40004] * 4), None, good, None) == -2
+    assert hd(C.byref(fake_ring()), good, None, arr([0x50008] * 4), None) == -2
+    assert hd(C.byref(fake_ring(mode=B.QUANT8)), good, None, good, None) == -1        # send-buffer scales missing
+    assert hd(C.byref(fake_ring(mode=9)), good, good, good, None) == -3
+    assert hd(C.byref(fake_ring(n=0, g=0, pay=0, sc=0)), None, None, None, None) == 0  # empty vector: nothing to do
+    direct = L.pipesgd_allreduce_direct
+    assert direct(C.byref(fake_ring()), None, None, None) == -1
+    assert direct(C.byref(fake_ring()), arr([0x40004] * 4), None, None) == -2
+    assert direct(C.byref(fake_ring(mode=B.QUANT8)), good, None, None) == -1
+    assert direct(C.byref(fake_ring(n=0, g=0, pay=0, sc=0)), None, None, None) == 0
+
+
 def test_codec_and_update_validation_errors():
     L = B.lib()
     assert L.pipesgd_compress(5, 0x1000, 10, 0x2000, None, None) == -3
