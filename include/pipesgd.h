@@ -9,7 +9,8 @@
  *
  * Conventions common to every entry point
  *   - Return value: 0 on success, a negative PIPESGD_ERR_* otherwise.  Nothing
- *     throws, aborts or logs.  On error nothing has been enqueued.
+ *     throws, aborts or logs.  Arguments are checked before the first launch:
+ *     on any error other than PIPESGD_ERR_HIP nothing has been enqueued.
  *   - "DEVICE" pointers are HIP device memory owned by the caller; the library
  *     allocates no device memory.  The only state it keeps is on the host: the
  *     launch-geometry table (see "tuning") and what the opaque pipesgd_overlap
