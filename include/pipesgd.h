@@ -323,9 +323,13 @@ int pipesgd_unpack(const pipesgd_segment *segments, uint64_t num, uint64_t total
  * (Eq. 4) as far as the two streams do not compete for the same resource.
  * width 1 is decentralised synchronous SGD: compute g[t], AllReduce, update with
  * A[t], one after the other (Eq. 2: l_up + l_comp + l_comm).
- * The caller keeps the two slot sets and alternates them: `ring` writes the
- * slot set of iteration t, `stale_*` name the slot set of iteration t-1 (an
- * all-zero set at t = 1), `fresh_*` the set `ring` writes (width 1 only).
+ * width K in 3..7 is Algorithm 1 with iteration dependency K: the update of
+ * iteration t waits for and applies A[t-(K-1)] (Eq. 3's regime; the paper finds
+ * K = 2 optimal).
+ * The caller keeps K slot sets (two for width 1 and 2) and rotates them: `ring`
+ * writes the slot set of iteration t, `stale_*` name the slot set of iteration
+ * t-(K-1) (an all-zero set while t < K), `fresh_*` the set `ring` writes (width
+ * 1 only).
  * The caller must not change g_local while an AllReduce that reads it may still
  * be running (pipesgd_runtime_sync, or double-buffer the gradients). */
 typedef struct pipesgd_runtime pipesgd_runtime;
@@ -333,7 +337,7 @@ typedef struct pipesgd_runtime pipesgd_runtime;
 typedef struct pipesgd_runtime_iter {
     const pipesgd_ring *ring;            /* AllReduce of this iteration (HOST struct) */
     int32_t  schedule;                   /* PIPESGD_STEPWISE / PIPESGD_FUSED */
-    int32_t  width;                      /* 2 = pipelined (staleness 1), 1 = synchronous */
+    int32_t  width;                      /* 2 = pipelined (staleness 1), 1 = synchronous, 3..7 = staleness width-1 */
     int32_t  replicas;                   /* model replicas to update (normally ring->workers) */
     int32_t  compute_workgroups;         /* workgroups the compute stand-in occupies (>= 1) */
     float    compute_us;                 /* duration of the compute stand-in, microseconds (0 = none) */

@@ -100,15 +100,17 @@ int pipesgd_synthetic_compute(float duration_us, int workgroups, void *stream)
 int pipesgd_runtime_iteration(pipesgd_runtime *rt, const pipesgd_runtime_iter *it)
 {
     if (!rt || !rt->ok || !it || !it->ring) return PIPESGD_ERR_ARG;
-    if ((it->width != 1 && it->width != 2) || it->reserved != 0) return PIPESGD_ERR_ARG;
+    if (it->width < 1 || it->width >= kEventRing || it->reserved != 0) return PIPESGD_ERR_ARG;
     const uint64_t t = rt->t + 1;                       // this call is iteration t (1-based)
     hipEvent_t sum_ready = rt->sum_ready[t % kEventRing];
     int rc;
     const int wg = it->compute_workgroups > 0 ? it->compute_workgroups : 1;
 
-    if (it->width == 2) {
+    if (it->width >= 2) {
         // Indexing: g[t] is the gradient evaluated at w[t-1]; A[t] = AllReduce(g[t]);
-        // w[t] = Update(w[t-1], A[t-1]).  (Alg. 1 counts the same steps one later.)
+        // w[t] = Update(w[t-1], A[t-(K-1)]), K = width = Alg. 1's iteration dependency
+        // (2 in the paper's optimal setting).  (Alg. 1 counts the same steps one later.)
+        const uint64_t lag = static_cast<uint64_t>(it->width - 1);
         // communication thread: g[t] was marked ready by the previous call's compute part
         if (t > 1 && hipStreamWaitEvent(rt->comm, rt->local_ready[t % kEventRing], 0) != hipSuccess) return PIPESGD_ERR_HIP;
         rc = pipesgd_allreduce_sim(it->ring, it->schedule, rt->comm);
@@ -116,9 +118,9 @@ int pipesgd_runtime_iteration(pipesgd_runtime *rt, const pipesgd_runtime_iter *i
         rc = pipesgd_synthetic_compute(it->wire_us, 1, rt->comm);          // time on the network
         if (rc != PIPESGD_OK) return rc;
         if (hipEventRecord(sum_ready, rt->comm) != hipSuccess) return PIPESGD_ERR_HIP;
-        // computation thread, meanwhile: wait for A[t-1], decompress + update -> w[t], then the
+        // computation thread, meanwhile: wait for A[t-(K-1)], decompress + update -> w[t], then the
         // stand-in for batch/forward/backward that yields g[t+1], and mark it ready
-        if (t > 1 && hipStreamWaitEvent(rt->compute, rt->sum_ready[(t - 1) % kEventRing], 0) != hipSuccess)
+        if (t > lag && hipStreamWaitEvent(rt->compute, rt->sum_ready[(t - lag) % kEventRing], 0) != hipSuccess)
             return PIPESGD_ERR_HIP;
         rc = pipesgd_apply_update_multi(it->ring->mode, it->replicas, it->stale_g_sum_c, it->stale_scales, it->ring->n,
                                         it->w, it->v, it->lr, it->momentum, it->grad_scale, rt->compute);

@@ -3,9 +3,9 @@ workers' gradient, payload, model and momentum buffers with PyTorch and strings
 the library calls together in the order of Algorithm 1 (arXiv 1811.03619).
 No arithmetic happens in this file.
 
-Iteration t (width 2, the paper's optimal pipeline):
-    A[t]  = AllReduce(g_local[t])          -> slot[t % 2]
-    w[t]  = Update(w[t-1], slot[(t-1) % 2])   (slot starts as zero)
+Iteration t (width K; K = 2 is the paper's optimal pipeline, K = 1 synchronous):
+    A[t]  = AllReduce(g_local[t])              -> slot[t % K]
+    w[t]  = Update(w[t-1], slot[(t-K+1) % K])     (slots start as zero)
 The two calls touch disjoint buffers, which is what lets the paper overlap
 them; here they are enqueued back to back on one stream.
 """
@@ -38,7 +38,7 @@ class PipeSgdSim:
     def __init__(self, mode: int, workers: int, n: int, lr: float, momentum: float = 0.0,
                  grad_scale: float = 1.0, width: int = 2, buckets: Optional[Sequence[Tuple[int, int]]] = None,
                  schedule: int = B.STEPWISE, device="cuda:0"):
-        assert width in (1, 2)
+        assert 1 <= width <= 7
         self.mode, self.p, self.n = mode, workers, n
         self.lr, self.momentum, self.grad_scale, self.width = lr, momentum, grad_scale, width
         self.schedule = schedule
@@ -49,7 +49,7 @@ class PipeSgdSim:
         self.g_local = [torch.zeros(max(n, 1), dtype=torch.float32, device=dev)[:n] for _ in range(workers)]
         self.w = [torch.zeros(max(n, 1), dtype=torch.float32, device=dev)[:n] for _ in range(workers)]
         self.v = [torch.zeros(max(n, 1), dtype=torch.float32, device=dev)[:n] for _ in range(workers)]
-        nslots = 2 if width == 2 else 1
+        nslots = width                                  # Alg. 1 keeps K result buffers
         self.slots = [[payload_empty(mode, n, dev) for _ in range(workers)] for _ in range(nslots)]
         self.slot_scales = [[torch.zeros(max(ns, 1), dtype=torch.float32, device=dev)[:ns] for _ in range(workers)]
                             for _ in range(nslots)]
@@ -132,8 +132,5 @@ class PipeSgdSim:
             self.t += 1
             return
         cur = self.allreduce(stream)
-        if self.width == 2:
-            self.update_from(1 - cur, stream)
-        else:
-            self.update_from(cur, stream)
+        self.update_from((cur + 1) % self.width, stream)        # the slot written width-1 iterations ago
         self.t += 1

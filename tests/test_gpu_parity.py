@@ -347,6 +347,23 @@ def run_both(orc, mode, grad_fn, w0, p, iters, lr, momentum, width, buckets=None
     return sim, ws_ref, vs_ref
 
 
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("width", [3, 4])
+def test_wider_pipelines_follow_algorithm_1(orc, mode, width):
+    # Alg. 1 with iteration dependency K = width > 2: the update of iteration t applies the
+    # aggregated gradient of iteration t-(K-1); the first K-1 updates are no-ops.  The gradient
+    # depends on the model, so a wrong staleness changes every later iterate.
+    p, n = 4, 4096 * 5 + 19
+    wstar = W.gaussian(n, 1.0, 31, (mode, 0, 0, 0))
+    grad_fn = lambda r, w, t: ((w - wstar) * np.float32(0.25 + 0.1 * r)).astype(np.float32)
+    w0 = np.zeros(n, np.float32)
+    sim, ws_ref, vs_ref = run_both(orc, mode, grad_fn, w0, p, 8, 0.05, 0.5, width)
+    for r in range(p):
+        assert_fp32_close_then_exact(sim.model(r), ws_ref[r], f"w r={r}")
+        assert_fp32_close_then_exact(sim.velocity(r), vs_ref[r], f"v r={r}")
+    assert not np.array_equal(ws_ref[0], w0)
+
+
 def test_config1_quadratic_ten_iterations(orc):
     # K = 4 workers, 1,048,576 parameters, lr 0.01, no momentum, no compression,
     # loss 0.5*||w - w*||^2: closed form s_10 = 0.6825982976 for staleness 1
@@ -540,12 +557,13 @@ def test_allreduce_pipelined_rejects_buckets_and_bad_arguments():
 # ------------------------------------------ Algorithm 1's two-thread runtime --
 
 @pytest.mark.parametrize("mode", MODES)
-@pytest.mark.parametrize("width", [1, 2])
+@pytest.mark.parametrize("width", [1, 2, 3, 5])
 def test_two_stream_runtime_matches_oracle(orc, mode, width):
-    p, n, lr, m, iters = 4, 4096 * 11 + 77, 0.01, 0.9, 5
+    p, n, lr, m, iters = 4, 4096 * 11 + 77, 0.01, 0.9, 5 if width <= 2 else 9
     grad_fn = lambda r, w, t: W.gaussian(n, 1e-3, 21, (mode, r, t, 0))
     w0 = W.gaussian(n, 0.05, 23)
-    sim = PipeSgdSim(mode, p, n, lr, m, 1.0, 2)          # two slot sets in both cases
+    K = max(width, 2)
+    sim = PipeSgdSim(mode, p, n, lr, m, 1.0, K)          # K slot sets (two also for the synchronous case)
     sim.set_model(w0)
     sync()
     rt = B.Runtime()
@@ -553,14 +571,24 @@ def test_two_stream_runtime_matches_oracle(orc, mode, width):
         rt.sync()                                        # gradients change: the previous AllReduce must be done
         sim.set_gradients([grad_fn(r, None, t) for r in range(p)])
         sync()
-        cur = t % 2
-        rt.iteration(sim.rings[cur], sim.updates[1 - cur], sim.updates[cur], B.STEPWISE, width, lr, m, 1.0,
+        cur = t % K
+        rt.iteration(sim.rings[cur], sim.updates[(cur + 1) % K], sim.updates[cur], B.STEPWISE, width, lr, m, 1.0,
                      compute_us=150.0, compute_workgroups=8)
     rt.sync()
     ws, vs = orc.pipe_sgd_run(mode, grad_fn, w0, p, iters, lr, m, 1.0, width)
     for r in range(p):
         assert_fp32_close_then_exact(sim.model(r), ws[r], f"w r={r}")
         assert_fp32_close_then_exact(sim.velocity(r), vs[r], f"v r={r}")
+    rt.close()
+
+
+def test_runtime_rejects_widths_it_has_no_events_for():
+    sim = PipeSgdSim(B.NONE, 2, 4096 * 2, 0.01, 0.0, 1.0, 2)
+    rt = B.Runtime()
+    for width in (0, -1, 8, 100):
+        with pytest.raises(B.PipeSgdError):
+            rt.iteration(sim.rings[0], sim.updates[1], sim.updates[0], B.STEPWISE, width, 0.01, 0.0)
+    rt.sync()
     rt.close()
 
 
