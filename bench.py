@@ -487,11 +487,23 @@ def study_two_thread_runtime(sim, B, torch, np, schedule, iters: int = 30):
     l_up = alone(lambda: sim.update_from(1))
     l_comm = alone(lambda: B.allreduce_sim(sim.rings[0], schedule))
 
+    # a third result-slot set for the width-3 leg (Alg. 1 keeps K of them)
+    from paper_1811_03619_amd.pipeline import payload_empty
+    ns = B.num_scales(sim.mode, sim.n)
+    slots3 = [payload_empty(sim.mode, sim.n, sim.device) for _ in range(p)]
+    scales3 = [torch.zeros(max(ns, 1), dtype=torch.float32, device=sim.device)[:ns] for _ in range(p)]
+    q8 = sim.mode == B.QUANT8
+    rings = list(sim.rings) + [B.make_ring(sim.mode, sim.n, sim.g_local, slots3, scales3 if q8 else None, sim.buckets)]
+    updates = list(sim.updates) + [B.UpdateArgs(slots3, scales3 if q8 else None, sim.w,
+                                                sim.v if sim.momentum != 0.0 else None)]
+
     def per_iter(width, compute_us, wire_us):
+        K = max(width, 2)
+
         def run(k):
             for i in range(k):
-                cur = i % 2
-                rt.iteration(sim.rings[cur], sim.updates[1 - cur], sim.updates[cur], schedule, width,
+                cur = i % K
+                rt.iteration(rings[cur], updates[(cur + 1) % K], updates[cur], schedule, width,
                              sim.lr, sim.momentum, sim.grad_scale, compute_us=compute_us, compute_workgroups=16,
                              wire_us=wire_us)
         run(4)
@@ -506,8 +518,10 @@ def study_two_thread_runtime(sim, B, torch, np, schedule, iters: int = 30):
         rows = []
         for l_comp in (0.0, 0.2, 0.4, 0.6, 0.8, 1.0, 1.4, 1.8):
             w2, w1 = per_iter(2, l_comp * 1e3, wire * 1e3), per_iter(1, l_comp * 1e3, wire * 1e3)
+            w3 = per_iter(3, l_comp * 1e3, wire * 1e3)
             lc = l_comm + wire
-            rows.append({"l_comp": l_comp, "pipelined": round(w2, 4), "synchronous": round(w1, 4),
+            rows.append({"l_comp": l_comp, "pipelined": round(w2, 4), "pipelined_width_3": round(w3, 4),
+                         "synchronous": round(w1, 4),
                          "eq4": round(B.model_pipe_time(1, l_up, l_comp, lc), 4),
                          "eq4_one_gpu": round(max(l_up + l_comm + l_comp, lc), 4),
                          "eq2": round(B.model_sync_time(1, l_up, l_comp, lc), 4),
