@@ -15,6 +15,7 @@ INCLUDE = os.path.join(ROOT, "include")
 LIB_PATH = os.path.join(_HERE, "libpipesgd.so")
 
 SOURCES = ["pipesgd_kernels.hip", "pipesgd_runtime.hip", "pipesgd_host.cpp"]
+HEADERS = ["pipesgd_device.hpp"]                      # private to csrc/; included by pipesgd_kernels.hip
 
 # One IEEE rounding per written operation: no contraction, no fast-math.
 # Packed-fp32 instruction selection is switched off on purpose.
@@ -34,7 +35,7 @@ def is_stale() -> bool:
     if not os.path.exists(LIB_PATH):
         return True
     t = os.path.getmtime(LIB_PATH)
-    deps = sources() + [os.path.join(INCLUDE, "pipesgd.h")]
+    deps = sources() + [os.path.join(CSRC, h) for h in HEADERS] + [os.path.join(INCLUDE, "pipesgd.h")]
     return any(os.path.getmtime(d) > t for d in deps)
 
 
