@@ -335,6 +335,14 @@ def time_phases(sim, B, torch, np, reps: int = 20):
     res["allreduce_fused"] = timed(lambda: B.allreduce_sim(ring, B.FUSED))
     if sim.schedule in (B.DIRECT, B.HALVING_DOUBLING):
         res["allreduce_selected_schedule"] = timed(lambda: sim.allreduce())
+    # the stand-alone codecs on one worker's gradient (pipesgd_compress / pipesgd_decompress)
+    from paper_1811_03619_amd.pipeline import payload_empty
+    ns = B.num_scales(sim.mode, sim.n)
+    pay = payload_empty(sim.mode, sim.n, sim.device)
+    sc = torch.zeros(max(ns, 1), dtype=torch.float32, device=sim.device)[:ns] if sim.mode == B.QUANT8 else None
+    back = torch.empty_like(sim.g_local[0])
+    res["compress_one_worker"] = timed(lambda: B.compress(sim.mode, sim.g_local[0], sim.n, pay, sc))
+    res["decompress_one_worker"] = timed(lambda: B.decompress(sim.mode, pay, sc, sim.n, back))
     res["update_all_replicas"] = timed(lambda: sim.update_from(1))
     one = B.UpdateArgs(sim.slots[1][:1], sim.slot_scales[1][:1] if sim.mode == B.QUANT8 else None, sim.w[:1],
                        sim.v[:1] if sim.momentum != 0.0 else None)

@@ -444,8 +444,8 @@ LaunchConfig g_cfg[kNumKinds][3] = {
     /* all-gather     */ {{128, 2, 0}, {256, 2, 0}, {256, 1, 0}},
     /* fused          */ {{256, 1, 0}, {256, 1, 0}, {256, 4, 0}},
     /* update         */ {{256, 1, 65536}, {256, 1, 65536}, {256, 1, 0}},
-    /* compress       */ {{256, 4, 0}, {256, 4, 0}, {256, 4, 0}},
-    /* decompress     */ {{256, 4, 0}, {256, 4, 0}, {256, 4, 0}},
+    /* compress       */ {{256, 4, 0}, {512, 2, 0}, {512, 2, 0}},
+    /* decompress     */ {{256, 4, 0}, {256, 2, 0}, {128, 2, 0}},
 };
 
 constexpr int kMaxLds = 159 * 1024;        // a CU has 160 KiB; leave room for the kernels' own few bytes
