@@ -343,6 +343,9 @@ def time_phases(sim, B, torch, np, reps: int = 20):
     back = torch.empty_like(sim.g_local[0])
     res["compress_one_worker"] = timed(lambda: B.compress(sim.mode, sim.g_local[0], sim.n, pay, sc))
     res["decompress_one_worker"] = timed(lambda: B.decompress(sim.mode, pay, sc, sim.n, back))
+    # ceiling probe with the library's own plain copy (NONE "compression"): 4n bytes in, 4n out, Gaussian data
+    res["plain_copy_one_gradient"] = timed(lambda: B.compress(B.NONE, sim.g_local[0], sim.n, back, None))
+    res["plain_copy_GBps"] = round(8.0 * sim.n / res["plain_copy_one_gradient"] / 1e6, 1)
     res["update_all_replicas"] = timed(lambda: sim.update_from(1))
     one = B.UpdateArgs(sim.slots[1][:1], sim.slot_scales[1][:1] if sim.mode == B.QUANT8 else None, sim.w[:1],
                        sim.v[:1] if sim.momentum != 0.0 else None)
