@@ -54,8 +54,12 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 #ifndef PIPESGD_NT_UPDATE
 #define PIPESGD_NT_UPDATE 1      // slot, w, v of the update: 2 GB streamed once
 #endif
+#ifndef PIPESGD_NT_CODEC_OUT
+#define PIPESGD_NT_CODEC_OUT 0   // output of the stand-alone codec calls: the hint costs 5-10 % while the output
+                                 // fits the memory-side cache (up to ~0.5 GB) and gains 5 % at 1.1 GB
+#endif
 constexpr bool kNtGrad = PIPESGD_NT_GRAD, kNtPayIn = PIPESGD_NT_PAYIN, kNtPayOut = PIPESGD_NT_PAYOUT,
-               kNtUpdate = PIPESGD_NT_UPDATE;
+               kNtUpdate = PIPESGD_NT_UPDATE, kNtCodecOut = PIPESGD_NT_CODEC_OUT;
 
 template <bool NT, typename V> __device__ __forceinline__ V ld(const V *p)
 {

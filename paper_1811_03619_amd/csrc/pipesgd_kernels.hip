@@ -292,7 +292,7 @@ __device__ __forceinline__ void compress_body(const float *src, const UnitRef &t
     load_f32<G, FULL, true>(src + t.elem0, t.len, x);
     float scale = 0.0f;
     if constexpr (MODE == PIPESGD_QUANT8) scale = tile_absmax<G>(x, red);
-    store_payload<MODE, G, FULL, false>(pay, sc, t.elem0, t.len, scale, x);
+    store_payload<MODE, G, FULL, kNtCodecOut>(pay, sc, t.elem0, t.len, scale, x);
 }
 
 template <int MODE, class G>
@@ -311,7 +311,7 @@ __device__ __forceinline__ void decompress_body(const void *pay, float scale, co
 {
     float x[G::kPerThread];
     load_payload<MODE, G, FULL, true>(pay, t.elem0, t.len, scale, x);
-    store_f32<G, FULL, false>(dst + t.elem0, t.len, x);
+    store_f32<G, FULL, kNtCodecOut>(dst + t.elem0, t.len, x);
 }
 
 template <int MODE, class G>
