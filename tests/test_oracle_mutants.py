@@ -14,7 +14,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SRC = os.path.join(ROOT, "oracle", "pipesgd_oracle.c")
 
 PIN_FILES = ["tests/test_oracle_codec.py", "tests/test_oracle_ring.py", "tests/test_oracle_update.py",
-             "tests/test_oracle_bucket.py", "tests/test_oracle_direct.py", "tests/test_oracle_hd.py"]
+             "tests/test_oracle_bucket.py", "tests/test_oracle_direct.py", "tests/test_oracle_hd.py", "tests/test_golden.py"]
 
 # (name, text to find, replacement)
 MUTANTS = [
