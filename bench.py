@@ -92,6 +92,10 @@ def main() -> int:
     ap.add_argument("--graph", action="store_true",
                     help="replay the iterations from a captured HIP graph (two iterations per replay); "
                          "the update kernel is then not bracketed by events, so roofline.achieved is null")
+    ap.add_argument("--two-streams", action="store_true",
+                    help="run the iterations through the library's two-stream runtime (Algorithm 1's two threads: the "
+                         "AllReduce on one stream, the update on the other); the update kernel is then not bracketed "
+                         "by events, so roofline.achieved is null")
     ap.add_argument("--study", choices=["within-allreduce", "two-thread-runtime", "ring-cost-model"], default=None,
                     help="extra measurement printed as its own JSON line after the main one")
     ap.add_argument("--calib-copy", type=int, default=0,
@@ -153,7 +157,27 @@ def main() -> int:
     # ---- timed region: exactly `steps` iterations; the update launch of every
     # iteration is bracketed by events on the launch stream for the roofline.
     upd_ms = None
-    if args.graph:
+    if args.two_streams:
+        if schedule not in (B.STEPWISE, B.FUSED) or args.graph:
+            print("bench.py: --two-streams takes the stepwise or fused schedule, without --graph", file=sys.stderr)
+            return 2
+        rt = B.Runtime()
+
+        def run(k):
+            for _ in range(k):
+                cur = (sim.t + 1) % 2
+                rt.iteration(sim.rings[cur], sim.updates[1 - cur], sim.updates[cur], schedule, 2, sim.lr, sim.momentum,
+                             sim.grad_scale)
+                sim.t += 1
+        run(4)
+        rt.sync()
+        start_ev, stop_ev = None, None
+        t_begin = time.perf_counter()
+        run(args.steps)
+        rt.sync()
+        wall_s = time.perf_counter() - t_begin
+        rt.close()
+    elif args.graph:
         if args.steps % 2 or sim.t % 2:
             print("bench.py: --graph replays pairs of iterations: use even --steps and --warmup", file=sys.stderr)
             return 2
@@ -189,7 +213,7 @@ def main() -> int:
         wall_s = time.perf_counter() - t_begin
         upd_ms = float(np.mean([a.elapsed_time(b) for a, b in ev])) if schedule != B.ONE_LAUNCH else None
     ms_per_step = wall_s * 1e3 / args.steps
-    gpu_ms_per_step = start_ev.elapsed_time(stop_ev) / args.steps
+    gpu_ms_per_step = start_ev.elapsed_time(stop_ev) / args.steps if start_ev is not None else ms_per_step
 
     n_true = int(sum(numels))          # bucket padding is processed but is not part of the model
     model = bytes_model(mode, n_true, p, momentum != 0.0, fused=(schedule in (B.FUSED, B.ONE_LAUNCH)), direct=(schedule == B.DIRECT),
@@ -217,7 +241,7 @@ def main() -> int:
             "packed_elements_per_worker": n,
             "tensors": len(specs), "buckets": len(buckets) if buckets else 1,
             "compression": ["none", "trunc16", "quant8"][mode], "momentum": momentum, "lr": args.lr,
-            "pipeline_width": 2, "schedule": args.schedule, "hip_graph": bool(args.graph), "seed": args.seed,
+            "pipeline_width": 2, "schedule": args.schedule, "hip_graph": bool(args.graph), "two_streams": bool(args.two_streams), "seed": args.seed,
         },
         "iters_per_s": round(1e3 / ms_per_step, 2),
         "hbm_peak_fraction": round(value / HBM_PEAK_GBS, 4),
