@@ -201,6 +201,21 @@ int pipesgd_allreduce_direct(const pipesgd_ring *ring, void *const *stage, float
 int pipesgd_allreduce_halving_doubling(const pipesgd_ring *ring, void *const *stage, float *const *stage_scales,
                                        float *const *partial, void *stream);
 
+/* Scratch that a schedule needs PER WORKER beyond the gradients and the result
+ * slots; the caller allocates it (the library allocates nothing) and passes it
+ * as the staging arguments of the entry point named below.  HOST arithmetic.
+ *   bytes[0]  payload-sized staging (recv / stage), = pipesgd_payload_bytes(mode, n)
+ *   bytes[1]  its per-block scales (recv_scales / stage_scales), QUANT8 only
+ *   bytes[2]  fp32 partial sums (partial), halving-doubling with more than two workers
+ * all zero for the ring schedules of pipesgd_allreduce_sim and for one worker.
+ * Returns PIPESGD_ERR_MODE for an unknown mode or schedule, PIPESGD_ERR_ARG for
+ * workers < 1 or a NULL table. */
+#define PIPESGD_WS_RING              0   /* pipesgd_allreduce_sim, both schedules, and pipesgd_iteration_fused */
+#define PIPESGD_WS_PIPELINED         1   /* pipesgd_allreduce_pipelined */
+#define PIPESGD_WS_DIRECT            2   /* pipesgd_allreduce_direct */
+#define PIPESGD_WS_HALVING_DOUBLING  3   /* pipesgd_allreduce_halving_doubling */
+int pipesgd_workspace_bytes(int schedule, int mode, uint64_t n, int workers, uint64_t bytes[3]);
+
 /* ---------------------------------------- pipelining within the AllReduce -- */
 
 /* Host-side resources (HIP events) of the two-stream schedule below.  No device

@@ -34,7 +34,7 @@ EXPORTS = [
     "pipesgd_runtime_stream", "pipesgd_synthetic_compute",
     "pipesgd_model_sync_time", "pipesgd_model_pipe_ideal_time", "pipesgd_model_pipe_time",
     "pipesgd_model_ring_comm_time", "pipesgd_model_scaling_efficiency", "pipesgd_iteration_fused", "pipesgd_allreduce_direct",
-    "pipesgd_allreduce_halving_doubling",
+    "pipesgd_allreduce_halving_doubling", "pipesgd_workspace_bytes",
 ]
 K_FIRST_SEND, K_REDUCE_SCATTER, K_ALLGATHER, K_FUSED, K_UPDATE, K_COMPRESS, K_DECOMPRESS = range(7)
 
@@ -158,6 +158,8 @@ def lib():
     L.pipesgd_model_ring_comm_time.argtypes = [i32, dbl, dbl, dbl, dbl, dbl, i32]
     L.pipesgd_allreduce_direct.restype = i32
     L.pipesgd_allreduce_direct.argtypes = [C.POINTER(RingStruct), vp, vp, vp]
+    L.pipesgd_workspace_bytes.restype = i32
+    L.pipesgd_workspace_bytes.argtypes = [i32, i32, u64, i32, C.POINTER(C.c_uint64)]
     L.pipesgd_allreduce_halving_doubling.restype = i32
     L.pipesgd_allreduce_halving_doubling.argtypes = [C.POINTER(RingStruct), vp, vp, vp, vp]
     L.pipesgd_iteration_fused.restype = i32
@@ -220,6 +222,16 @@ def payload_bytes(mode: int, n: int) -> int:
 
 def num_scales(mode: int, n: int) -> int:
     return int(lib().pipesgd_num_scales(mode, n))
+
+
+WS_RING, WS_PIPELINED, WS_DIRECT, WS_HALVING_DOUBLING = 0, 1, 2, 3
+
+
+def workspace_bytes(schedule: int, mode: int, n: int, workers: int) -> Tuple[int, int, int]:
+    """(payload staging, scales staging, fp32 partial sums) bytes per worker."""
+    out = (C.c_uint64 * 3)()
+    check(lib().pipesgd_workspace_bytes(schedule, mode, n, workers, out), "pipesgd_workspace_bytes")
+    return int(out[0]), int(out[1]), int(out[2])
 
 
 def compress(mode: int, src, n: int, payload, scales=None, stream=None) -> None:

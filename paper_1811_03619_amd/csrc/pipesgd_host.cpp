@@ -47,6 +47,19 @@ uint64_t pipesgd_num_scales(int mode, uint64_t n)
     return mode == PIPESGD_QUANT8 ? (n + kTile - 1) / kTile : 0;
 }
 
+int pipesgd_workspace_bytes(int schedule, int mode, uint64_t n, int workers, uint64_t bytes[3])
+{
+    if (mode != PIPESGD_NONE && mode != PIPESGD_TRUNC16 && mode != PIPESGD_QUANT8) return PIPESGD_ERR_MODE;
+    if (schedule < PIPESGD_WS_RING || schedule > PIPESGD_WS_HALVING_DOUBLING) return PIPESGD_ERR_MODE;
+    if (workers < 1 || !bytes) return PIPESGD_ERR_ARG;
+    bytes[0] = bytes[1] = bytes[2] = 0;
+    if (schedule == PIPESGD_WS_RING || workers == 1) return PIPESGD_OK;
+    bytes[0] = pipesgd_payload_bytes(mode, n);
+    bytes[1] = 4 * pipesgd_num_scales(mode, n);
+    if (schedule == PIPESGD_WS_HALVING_DOUBLING && workers > 2) bytes[2] = 4 * n;
+    return PIPESGD_OK;
+}
+
 int pipesgd_bucket_plan(const uint64_t *numels, uint64_t num_tensors, uint64_t bucket_elems,
                         pipesgd_bucket *buckets, uint64_t max_buckets,
                         uint64_t *tensor_offsets, uint64_t *n_packed)

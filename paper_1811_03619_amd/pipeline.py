@@ -65,6 +65,11 @@ class PipeSgdSim:
             self.stage_scales = [torch.zeros(max(ns, 1), dtype=torch.float32, device=dev)[:ns] for _ in range(workers)]
         if schedule == B.HALVING_DOUBLING and workers > 2:      # fp32 partial sums between halving rounds
             self.partial = [torch.zeros(max(n, 1), dtype=torch.float32, device=dev)[:n] for _ in range(workers)]
+        if self.stage is not None and workers > 1:              # sizes as the library states them
+            ws = B.workspace_bytes(B.WS_DIRECT if schedule == B.DIRECT else B.WS_HALVING_DOUBLING, mode, n, workers)
+            assert ws[0] == self.stage[0].numel() * self.stage[0].element_size()
+            assert ws[1] == (self.stage_scales[0].numel() * 4 if mode == B.QUANT8 else 0)
+            assert ws[2] == (self.partial[0].numel() * 4 if self.partial is not None else 0)
         self.t = 0
 
     # -- data in / out (host <-> device copies; plumbing) --

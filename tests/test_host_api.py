@@ -155,6 +155,24 @@ def test_extra_schedules_validate_before_launching():
     assert direct(C.byref(fake_ring(n=0, g=0, pay=0, sc=0)), None, None, None) == 0
 
 
+@pytest.mark.parametrize("mode", [B.NONE, B.TRUNC16, B.QUANT8])
+@pytest.mark.parametrize("n", [0, 5, 4096, 4097, 60965224])
+def test_workspace_bytes(mode, n):
+    cb = {B.NONE: 4, B.TRUNC16: 2, B.QUANT8: 1}[mode]
+    ns = -(-n // 4096) if mode == B.QUANT8 else 0
+    for p in (1, 2, 4, 16):
+        assert B.workspace_bytes(B.WS_RING, mode, n, p) == (0, 0, 0)
+        for sched in (B.WS_PIPELINED, B.WS_DIRECT, B.WS_HALVING_DOUBLING):
+            want = (0, 0, 0) if p == 1 else (cb * n, 4 * ns, 4 * n if sched == B.WS_HALVING_DOUBLING and p > 2 else 0)
+            assert B.workspace_bytes(sched, mode, n, p) == want
+    L = B.lib()
+    out = (C.c_uint64 * 3)()
+    assert L.pipesgd_workspace_bytes(9, mode, n, 4, out) == -3
+    assert L.pipesgd_workspace_bytes(B.WS_DIRECT, 7, n, 4, out) == -3
+    assert L.pipesgd_workspace_bytes(B.WS_DIRECT, mode, n, 0, out) == -1
+    assert L.pipesgd_workspace_bytes(B.WS_DIRECT, mode, n, 4, None) == -1
+
+
 def test_codec_and_update_validation_errors():
     L = B.lib()
     assert L.pipesgd_compress(5, 0x1000, 10, 0x2000, None, None) == -3
