@@ -96,7 +96,10 @@ def main() -> int:
                     help="run the iterations through the library's two-stream runtime (Algorithm 1's two threads: the "
                          "AllReduce on one stream, the update on the other); the update kernel is then not bracketed "
                          "by events, so roofline.achieved is null")
-    ap.add_argument("--study", choices=["within-allreduce", "two-thread-runtime", "ring-cost-model"], default=None,
+    ap.add_argument("--no-stagger", action="store_true",
+                    help="place every buffer at the start of a 4 KiB page instead of staggering them by multiples of "
+                         "256 bytes (for comparison)")
+    ap.add_argument("--study", choices=["within-allreduce", "two-thread-runtime", "ring-cost-model", "size-sweep"], default=None,
                     help="extra measurement printed as its own JSON line after the main one")
     ap.add_argument("--calib-copy", type=int, default=0,
                     help="after the timed region, launch this many plain copies of one worker's gradient "
@@ -145,7 +148,7 @@ def main() -> int:
     w0 = W.gaussian(n, 0.05, args.seed, (cfg, 99, 0, 0))
     gen_s = time.time() - t0
 
-    sim = PipeSgdSim(mode, p, n, args.lr, momentum, 1.0, 2, buckets, schedule)
+    sim = PipeSgdSim(mode, p, n, args.lr, momentum, 1.0, 2, buckets, schedule, stagger=not args.no_stagger)
     sim.set_gradients(grads)
     sim.set_model(w0)
     torch.cuda.synchronize()
@@ -241,7 +244,7 @@ def main() -> int:
             "packed_elements_per_worker": n,
             "tensors": len(specs), "buckets": len(buckets) if buckets else 1,
             "compression": ["none", "trunc16", "quant8"][mode], "momentum": momentum, "lr": args.lr,
-            "pipeline_width": 2, "schedule": args.schedule, "hip_graph": bool(args.graph), "two_streams": bool(args.two_streams), "seed": args.seed,
+            "pipeline_width": 2, "schedule": args.schedule, "hip_graph": bool(args.graph), "two_streams": bool(args.two_streams), "staggered_buffers": not args.no_stagger, "seed": args.seed,
         },
         "iters_per_s": round(1e3 / ms_per_step, 2),
         "hbm_peak_fraction": round(value / HBM_PEAK_GBS, 4),
@@ -275,6 +278,9 @@ def main() -> int:
 
     if args.study == "two-thread-runtime":
         study = study_two_thread_runtime(sim, B, torch, np, schedule)
+
+    if args.study == "size-sweep":
+        study = study_size_sweep(B, torch, np, mode, p, momentum, args.seed)
 
     if args.study == "ring-cost-model":
         study = study_ring_cost_model(B, torch, np, mode, n, p, args.seed)
@@ -445,6 +451,40 @@ def study_within_allreduce(sim, B, torch, np, mode, n, n_true, p, reps: int = 15
     rt.close()
     ov.close()
     return res
+
+
+def study_size_sweep(B, torch, np, mode, p, momentum, seed, reps: int = 20):
+    """Whole iteration and update launch against the gradient length: where the
+    path leaves the launch-bound regime and where the memory-side cache stops
+    helping."""
+    from paper_1811_03619_amd.pipeline import PipeSgdSim
+    rows = []
+    for m in (1 << 16, 1 << 18, 1 << 20, 1 << 22, 1 << 24, 1 << 25, 1 << 26, 1 << 27, 1 << 28):
+        sim = PipeSgdSim(mode, p, m, 0.01, momentum)
+        for r in range(p):
+            sim.g_local[r].normal_(0.0, 1e-3, generator=torch.Generator(device=sim.device).manual_seed(seed + r))
+        for _ in range(4):
+            sim.iteration()
+        torch.cuda.synchronize()
+        it_ms, up_ms = [], []
+        for _ in range(reps):
+            a, b, c = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+            a.record()
+            cur = sim.allreduce()
+            b.record()
+            sim.update_from(1 - cur)
+            c.record()
+            sim.t += 1
+            torch.cuda.synchronize()
+            it_ms.append(a.elapsed_time(c)); up_ms.append(b.elapsed_time(c))
+        model = bytes_model(mode, m, p, momentum != 0.0)
+        it, up = float(np.median(it_ms)), float(np.median(up_ms))
+        rows.append({"elements_per_worker": m, "bytes_per_iter": int(model["total"]), "iteration_ms": round(it, 5),
+                     "iteration_GBps": round(model["total"] / it / 1e6, 1), "update_ms": round(up, 5),
+                     "update_GBps": round(model["update"] / up / 1e6, 1)})
+        del sim
+        torch.cuda.empty_cache()
+    return {"study": "size-sweep", "workers": p, "mode": mode, "rows": rows}
 
 
 def study_ring_cost_model(B, torch, np, mode, n, p, seed, reps: int = 30):

@@ -443,7 +443,7 @@ LaunchConfig g_cfg[kNumKinds][3] = {
     /* reduce-scatter */ {{128, 2, 0}, {128, 2, 0}, {256, 4, 32768}},
     /* all-gather     */ {{128, 2, 0}, {256, 2, 0}, {256, 1, 0}},
     /* fused          */ {{256, 1, 0}, {256, 1, 0}, {256, 4, 0}},
-    /* update         */ {{256, 1, 65536}, {256, 1, 65536}, {256, 1, 0}},
+    /* update         */ {{256, 1, 65536}, {64, 4, 32768}, {64, 4, 32768}},
     /* compress       */ {{256, 4, 0}, {512, 2, 0}, {512, 2, 0}},
     /* decompress     */ {{256, 4, 0}, {256, 2, 0}, {128, 2, 0}},
 };
