@@ -280,7 +280,7 @@ def main() -> int:
         study = study_two_thread_runtime(sim, B, torch, np, schedule)
 
     if args.study == "size-sweep":
-        study = study_size_sweep(B, torch, np, mode, p, momentum, args.seed)
+        study = study_size_sweep(B, torch, np, mode, p, momentum, args.seed, stagger=not args.no_stagger)
 
     if args.study == "ring-cost-model":
         study = study_ring_cost_model(B, torch, np, mode, n, p, args.seed)
@@ -453,14 +453,14 @@ def study_within_allreduce(sim, B, torch, np, mode, n, n_true, p, reps: int = 15
     return res
 
 
-def study_size_sweep(B, torch, np, mode, p, momentum, seed, reps: int = 20):
+def study_size_sweep(B, torch, np, mode, p, momentum, seed, reps: int = 20, stagger: bool = True):
     """Whole iteration and update launch against the gradient length: where the
     path leaves the launch-bound regime and where the memory-side cache stops
     helping."""
     from paper_1811_03619_amd.pipeline import PipeSgdSim
     rows = []
     for m in (1 << 16, 1 << 18, 1 << 20, 1 << 22, 1 << 24, 1 << 25, 1 << 26, 1 << 27, 1 << 28):
-        sim = PipeSgdSim(mode, p, m, 0.01, momentum)
+        sim = PipeSgdSim(mode, p, m, 0.01, momentum, stagger=stagger)
         for r in range(p):
             sim.g_local[r].normal_(0.0, 1e-3, generator=torch.Generator(device=sim.device).manual_seed(seed + r))
         for _ in range(4):
@@ -484,7 +484,7 @@ def study_size_sweep(B, torch, np, mode, p, momentum, seed, reps: int = 20):
                      "update_GBps": round(model["update"] / up / 1e6, 1)})
         del sim
         torch.cuda.empty_cache()
-    return {"study": "size-sweep", "workers": p, "mode": mode, "rows": rows}
+    return {"study": "size-sweep", "workers": p, "mode": mode, "staggered_buffers": stagger, "rows": rows}
 
 
 def study_ring_cost_model(B, torch, np, mode, n, p, seed, reps: int = 30):
