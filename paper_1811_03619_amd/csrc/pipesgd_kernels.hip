@@ -433,17 +433,17 @@ struct LaunchConfig {
     int lds_bytes;           // dynamic LDS reserved per workgroup: caps resident workgroups per CU
 };
 
-// Defaults from sweeps on MI355X inside the whole iteration loop (NONE at 25.6M
-// elements per worker, TRUNC16 at 61M, QUANT8 at 138M; p = 4).  The update wants
-// small workgroups (one quad per thread) and, for the 16-byte-per-quad streams,
-// at most two resident workgroups' worth of LDS reservation per CU; the hop
-// kernels are nearly flat across geometries.  [kind][mode]
+// Defaults from sweeps on MI355X (NONE at 25.6M elements per worker, TRUNC16 at
+// 61M, QUANT8 at 138M; p = 4; buffers staggered within the 4 KiB channel
+// interleave).  The update is fastest with about 24-30 KiB of loads in flight per
+// compute unit: small workgroups and an LDS reservation that admits two or three
+// of them per CU.  The hop kernels are nearly flat across geometries.  [kind][mode]
 LaunchConfig g_cfg[kNumKinds][3] = {
     /* first send     */ {{256, 4, 0}, {128, 2, 0}, {512, 2, 32768}},
     /* reduce-scatter */ {{128, 2, 0}, {128, 2, 0}, {256, 4, 32768}},
     /* all-gather     */ {{128, 2, 0}, {256, 2, 0}, {256, 1, 0}},
     /* fused          */ {{256, 1, 0}, {256, 1, 0}, {256, 4, 0}},
-    /* update         */ {{256, 1, 65536}, {64, 4, 32768}, {64, 4, 32768}},
+    /* update         */ {{256, 1, 65536}, {64, 4, 53248}, {64, 4, 53248}},
     /* compress       */ {{256, 4, 0}, {512, 2, 0}, {512, 2, 0}},
     /* decompress     */ {{256, 4, 0}, {256, 2, 0}, {128, 2, 0}},
 };
