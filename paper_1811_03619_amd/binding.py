@@ -34,7 +34,7 @@ EXPORTS = [
     "pipesgd_runtime_stream", "pipesgd_synthetic_compute",
     "pipesgd_model_sync_time", "pipesgd_model_pipe_ideal_time", "pipesgd_model_pipe_time",
     "pipesgd_model_ring_comm_time", "pipesgd_model_scaling_efficiency", "pipesgd_iteration_fused", "pipesgd_allreduce_direct",
-    "pipesgd_allreduce_halving_doubling", "pipesgd_workspace_bytes",
+    "pipesgd_allreduce_halving_doubling", "pipesgd_workspace_bytes", "pipesgd_placement_offset",
 ]
 K_FIRST_SEND, K_REDUCE_SCATTER, K_ALLGATHER, K_FUSED, K_UPDATE, K_COMPRESS, K_DECOMPRESS = range(7)
 
@@ -158,6 +158,8 @@ def lib():
     L.pipesgd_model_ring_comm_time.argtypes = [i32, dbl, dbl, dbl, dbl, dbl, i32]
     L.pipesgd_allreduce_direct.restype = i32
     L.pipesgd_allreduce_direct.argtypes = [C.POINTER(RingStruct), vp, vp, vp]
+    L.pipesgd_placement_offset.restype = u64
+    L.pipesgd_placement_offset.argtypes = [i32, i32, i32]
     L.pipesgd_workspace_bytes.restype = i32
     L.pipesgd_workspace_bytes.argtypes = [i32, i32, u64, i32, C.POINTER(C.c_uint64)]
     L.pipesgd_allreduce_halving_doubling.restype = i32
@@ -225,6 +227,13 @@ def num_scales(mode: int, n: int) -> int:
 
 
 WS_RING, WS_PIPELINED, WS_DIRECT, WS_HALVING_DOUBLING = 0, 1, 2, 3
+(BUF_GRADIENT, BUF_W, BUF_V, BUF_SLOT_A, BUF_SLOT_B, BUF_SCALES_A, BUF_SCALES_B, BUF_STAGE, BUF_STAGE_SC,
+ BUF_PARTIAL) = range(10)
+
+
+def placement_offset(kind: int, worker: int, workers: int) -> int:
+    """Byte offset within a 4 KiB page at which this buffer should start (advisory)."""
+    return int(lib().pipesgd_placement_offset(kind, worker, workers))
 
 
 def workspace_bytes(schedule: int, mode: int, n: int, workers: int) -> Tuple[int, int, int]:

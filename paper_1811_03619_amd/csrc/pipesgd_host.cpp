@@ -47,6 +47,22 @@ uint64_t pipesgd_num_scales(int mode, uint64_t n)
     return mode == PIPESGD_QUANT8 ? (n + kTile - 1) / kTile : 0;
 }
 
+uint64_t pipesgd_placement_offset(int kind, int worker, int workers)
+{
+    if (kind < PIPESGD_BUF_GRADIENT || kind > PIPESGD_BUF_PARTIAL || worker < 0 || workers < 1 || worker >= workers)
+        return 0;
+    // Ring neighbours must differ: colour the cycle of workers with two colours, and the
+    // last worker of an odd ring with a third.
+    const int colour = (workers > 1 && workers % 2 == 1 && worker == workers - 1) ? 2 : worker % 2;
+    // Three positions per kind; kinds that one workgroup touches together get different
+    // triples: gradient | slot | slot of the neighbour, and slot | w | v.  The staging
+    // buffers of the other schedules reuse the triples of w and v, which no AllReduce
+    // kernel touches; the tiny scale arrays share the last position.
+    static const int base[10] = {0, 3, 6, 9, 12, 15, 15, 3, 15, 6};
+    const int pos = base[kind] == 15 ? 15 : base[kind] + colour;
+    return 256ull * static_cast<uint64_t>(pos);
+}
+
 int pipesgd_workspace_bytes(int schedule, int mode, uint64_t n, int workers, uint64_t bytes[3])
 {
     if (mode != PIPESGD_NONE && mode != PIPESGD_TRUNC16 && mode != PIPESGD_QUANT8) return PIPESGD_ERR_MODE;

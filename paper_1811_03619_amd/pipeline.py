@@ -27,22 +27,17 @@ def payload_empty(mode: int, n: int, device) -> torch.Tensor:
     return torch.zeros(max(n, 1), dtype=_PAYLOAD_TORCH[mode], device=device)[:n]
 
 
-# Placement.  PyTorch hands out large buffers at multiples of 2 MiB, so the streams a
-# workgroup touches together (a worker's gradient, its slot, the neighbour's slot; or slot,
-# w and v) would all sit at the same offset within the 4 KiB over which HBM channels
-# interleave and queue up on one channel at a time.  Buffers of different kinds and of
-# neighbouring workers therefore start at different multiples of 256 bytes within a 4 KiB
-# page (measured on MI355X: +2 to +2.5 % on the update kernel, more on power-of-two sizes).
-_KIND_G, _KIND_W, _KIND_V, _KIND_SLOT, _KIND_SCALES, _KIND_STAGE, _KIND_PARTIAL = 0, 1, 2, 3, 5, 7, 9
-
-
-def staggered_zeros(count: int, dtype: torch.dtype, device, kind: int, r: int, stagger: bool = True) -> torch.Tensor:
-    """count zero elements of dtype whose first byte sits 256 * ((3*kind + r) mod 16) bytes
-    into a 4 KiB page (stagger=False: at the page start)."""
+# Placement.  PyTorch hands out large buffers at multiples of 2 MiB; the library's
+# pipesgd_placement_offset says where within a 4 KiB page each buffer should start so that
+# the streams a workgroup touches together do not queue on one HBM channel.
+def staggered_zeros(count: int, dtype: torch.dtype, device, kind: int, r: int, workers: int,
+                    stagger: bool = True) -> torch.Tensor:
+    """count zero elements of dtype, starting at the advised offset within a 4 KiB page
+    (stagger=False: at the page start)."""
     itemsize = torch.empty(0, dtype=dtype).element_size()
     nbytes = count * itemsize
     raw = torch.zeros(nbytes + 2 * 4096, dtype=torch.uint8, device=device)
-    off = (-raw.data_ptr()) % 4096 + (256 * ((3 * kind + r) % 16) if stagger else 0)
+    off = (-raw.data_ptr()) % 4096 + (B.placement_offset(kind, r, workers) if stagger else 0)
     return raw[off:off + nbytes].view(dtype)
 
 
@@ -66,13 +61,13 @@ class PipeSgdSim:
         dev = self.device
         ns = B.num_scales(mode, n)
         f32, pay_t = torch.float32, _PAYLOAD_TORCH[mode]
-        z = lambda count, dtype, kind, r: staggered_zeros(count, dtype, dev, kind, r, stagger)
-        self.g_local = [z(n, f32, _KIND_G, r) for r in range(workers)]
-        self.w = [z(n, f32, _KIND_W, r) for r in range(workers)]
-        self.v = [z(n, f32, _KIND_V, r) for r in range(workers)]
+        z = lambda count, dtype, kind, r: staggered_zeros(count, dtype, dev, kind, r, workers, stagger)
+        self.g_local = [z(n, f32, B.BUF_GRADIENT, r) for r in range(workers)]
+        self.w = [z(n, f32, B.BUF_W, r) for r in range(workers)]
+        self.v = [z(n, f32, B.BUF_V, r) for r in range(workers)]
         nslots = width                                  # Alg. 1 keeps K result buffers
-        self.slots = [[z(n, pay_t, _KIND_SLOT + (i % 2), r) for r in range(workers)] for i in range(nslots)]
-        self.slot_scales = [[z(ns, f32, _KIND_SCALES + (i % 2), r) for r in range(workers)] for i in range(nslots)]
+        self.slots = [[z(n, pay_t, B.BUF_SLOT_A + (i % 2), r) for r in range(workers)] for i in range(nslots)]
+        self.slot_scales = [[z(ns, f32, B.BUF_SCALES_A + (i % 2), r) for r in range(workers)] for i in range(nslots)]
         self.rings = [B.make_ring(mode, n, self.g_local, self.slots[i],
                                   self.slot_scales[i] if mode == B.QUANT8 else None, self.buckets)
                       for i in range(nslots)]
@@ -81,10 +76,10 @@ class PipeSgdSim:
                         for i in range(nslots)]
         self.stage = self.stage_scales = self.partial = None
         if schedule in (B.DIRECT, B.HALVING_DOUBLING):  # send buffers of the one-exchange / halving-doubling schedules
-            self.stage = [z(n, pay_t, _KIND_STAGE, r) for r in range(workers)]
-            self.stage_scales = [z(ns, f32, _KIND_STAGE + 1, r) for r in range(workers)]
+            self.stage = [z(n, pay_t, B.BUF_STAGE, r) for r in range(workers)]
+            self.stage_scales = [z(ns, f32, B.BUF_STAGE_SC, r) for r in range(workers)]
         if schedule == B.HALVING_DOUBLING and workers > 2:      # fp32 partial sums between halving rounds
-            self.partial = [z(n, f32, _KIND_PARTIAL, r) for r in range(workers)]
+            self.partial = [z(n, f32, B.BUF_PARTIAL, r) for r in range(workers)]
         if self.stage is not None and workers > 1:              # sizes as the library states them
             ws = B.workspace_bytes(B.WS_DIRECT if schedule == B.DIRECT else B.WS_HALVING_DOUBLING, mode, n, workers)
             assert ws[0] == self.stage[0].numel() * self.stage[0].element_size()

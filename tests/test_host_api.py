@@ -173,6 +173,26 @@ def test_workspace_bytes(mode, n):
     assert L.pipesgd_workspace_bytes(B.WS_DIRECT, mode, n, 4, None) == -1
 
 
+def test_placement_offsets_separate_the_streams_of_a_workgroup():
+    off = B.placement_offset
+    for p in range(1, 17):
+        for r in range(p):
+            for slot in (B.BUF_SLOT_A, B.BUF_SLOT_B):
+                # a ring hop of worker r: its gradient, its slot, the neighbour's slot
+                hop = {off(B.BUF_GRADIENT, r, p), off(slot, r, p)}
+                if p > 1:
+                    hop.add(off(slot, (r - 1) % p, p))
+                assert len(hop) == (3 if p > 1 else 2), (p, r, slot)
+                # the update of replica r: slot, w, v
+                assert len({off(slot, r, p), off(B.BUF_W, r, p), off(B.BUF_V, r, p)}) == 3, (p, r, slot)
+                # the one-exchange and halving-doubling schedules: gradient, send buffer, partial sums, slot
+                assert len({off(B.BUF_GRADIENT, r, p), off(B.BUF_STAGE, r, p), off(B.BUF_PARTIAL, r, p),
+                            off(slot, r, p)}) == 4
+            for kind in range(10):
+                assert off(kind, r, p) % 256 == 0 and 0 <= off(kind, r, p) < 4096
+    assert off(-1, 0, 4) == 0 and off(10, 0, 4) == 0 and off(0, -1, 4) == 0 and off(0, 4, 4) == 0 and off(0, 0, 0) == 0
+
+
 def test_codec_and_update_validation_errors():
     L = B.lib()
     assert L.pipesgd_compress(5, 0x1000, 10, 0x2000, None, None) == -3
