@@ -193,6 +193,19 @@ def test_placement_offsets_separate_the_streams_of_a_workgroup():
     assert off(-1, 0, 4) == 0 and off(10, 0, 4) == 0 and off(0, -1, 4) == 0 and off(0, 4, 4) == 0 and off(0, 0, 0) == 0
 
 
+def test_plumbing_places_buffers_where_the_library_advises():
+    import torch
+    from paper_1811_03619_amd.pipeline import staggered_zeros
+    for kind in (B.BUF_GRADIENT, B.BUF_V, B.BUF_SLOT_B, B.BUF_PARTIAL):
+        for r, p in ((0, 4), (3, 4), (4, 5), (7, 8)):
+            for dtype in (torch.float32, torch.int16, torch.int8):
+                t = staggered_zeros(1000, dtype, "cpu", kind, r, p)
+                assert t.numel() == 1000 and t.dtype == dtype and int(t.abs().sum()) == 0
+                assert t.data_ptr() % 4096 == B.placement_offset(kind, r, p)
+                assert staggered_zeros(1000, dtype, "cpu", kind, r, p, stagger=False).data_ptr() % 4096 == 0
+    assert staggered_zeros(0, torch.float32, "cpu", 0, 0, 1).numel() == 0
+
+
 def test_codec_and_update_validation_errors():
     L = B.lib()
     assert L.pipesgd_compress(5, 0x1000, 10, 0x2000, None, None) == -3
