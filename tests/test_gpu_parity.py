@@ -3,6 +3,8 @@ element by element on the same seeded inputs.  Sizes span several 4096-element
 tiles and a ragged tail; edge cases: empty, one element, fewer elements than
 workers, empty ring blocks, 16 workers, special floating-point values.
 """
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -890,7 +892,8 @@ def test_pipe_sgd_run_with_halving_doubling(orc, mode):
 
 # ------------------------------------------------------------ random cases --
 
-@pytest.mark.parametrize("case", range(24))
+# PIPESGD_RANDOM_CASES=N widens the sweep for an occasional longer run
+@pytest.mark.parametrize("case", range(int(os.environ.get("PIPESGD_RANDOM_CASES", "24"))))
 def test_random_shapes_all_schedules(orc, case):
     # seeded random worker counts, lengths, bucket layouts and modes; every
     # AllReduce schedule and the update against the oracle
