@@ -389,8 +389,6 @@ def study_within_allreduce(sim, B, torch, np, mode, n, n_true, p, reps: int = 15
     hop's compressed payload into the receiver's staging buffer (the stand-in for
     the wire) on one stream, stage 2 (decompress, sum, compress) runs on another
     on what has arrived.  Reports how much of the shorter stage the overlap hides."""
-    if sim.buckets:
-        return {"study": "within-allreduce", "skipped": "single-bucket rings only"}
     from paper_1811_03619_amd.pipeline import payload_empty
     dev = sim.device
     ns = B.num_scales(mode, n)

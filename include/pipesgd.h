@@ -259,7 +259,8 @@ void pipesgd_overlap_destroy(pipesgd_overlap *ov);
  * GPU; it exists to measure how much of the codec time the transfer hides.
  * recv / recv_scales: HOST arrays of p DEVICE buffers, each as large as a result
  * slot (payload of n elements / its scales); contents are scratch.
- * Only single-bucket rings.  On return both streams hold work; compute_stream
+ * Buckets are supported (a sub-block is a range of the ring block's tiles, counted
+ * across buckets).  On return both streams hold work; compute_stream
  * is made to wait for the end of it, and wire_stream for everything enqueued on
  * compute_stream before the call.  wire_stream may equal compute_stream (no
  * overlap: the sequential baseline).

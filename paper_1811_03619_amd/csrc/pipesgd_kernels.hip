@@ -1034,8 +1034,7 @@ int pipesgd_allreduce_pipelined(const pipesgd_ring *ring, void *const *recv, flo
     RingArgs ra; BucketTable bt; uint64_t slots = 0;
     int rc = prepare_ring(ring, ra, bt, slots);
     if (rc != PIPESGD_OK) return rc;
-    if (!ov || segments < 1 || wire_workgroups < 0 || !(link_us_per_mib >= 0.0f) || ring->num_buckets > 1)
-        return PIPESGD_ERR_ARG;
+    if (!ov || segments < 1 || wire_workgroups < 0 || !(link_us_per_mib >= 0.0f)) return PIPESGD_ERR_ARG;
     const int mode = ring->mode, p = ring->workers;
     if (slots == 0) return PIPESGD_OK;
     if (p > 1) {

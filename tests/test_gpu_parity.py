@@ -539,15 +539,43 @@ def test_allreduce_pipelined_equals_oracle(orc, mode, p, n, segments, two_stream
     ov.close()
 
 
-def test_allreduce_pipelined_rejects_buckets_and_bad_arguments():
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("segments", [1, 3, 7])
+def test_allreduce_pipelined_with_buckets(orc, mode, segments):
+    # sub-blocks are tile ranges counted across buckets: some sub-blocks span a bucket boundary
+    p = 4
+    specs = W.scaled_config(5, 8)
+    numels = [s.numel for s in specs]
+    buckets, offs, N = B.bucket_plan(numels, 1 << 16)
+    assert len(buckets) > 3
+    packed = [orc.pack(W.gradient_tensors_for(specs, 5, r, seed=6), offs, N) for r in range(p)]
+    want = orc.allreduce_bucketed(mode, packed, buckets)
+    g_dev = [up(g) for g in packed]
+    slots = [pay_buf(mode, N, poison=False) for _ in range(p)]
+    scs = [dev_zeros(B.num_scales(mode, N)) for _ in range(p)]
+    recv = [pay_buf(mode, N) for _ in range(p)]
+    recv_sc = [dev_zeros(B.num_scales(mode, N), fill=-2.0) for _ in range(p)]
+    ring = B.make_ring(mode, N, g_dev, slots, scs if mode == B.QUANT8 else None, buckets)
+    ov, rt = B.Overlap(), B.Runtime()
+    B.allreduce_pipelined(ring, recv, recv_sc if mode == B.QUANT8 else None, segments, ov, rt.stream(0), rt.stream(1),
+                          link_us_per_mib=10.0)
+    rt.sync()
+    sync()
+    for r in range(p):
+        if mode == B.NONE:
+            assert_fp32_close_then_exact(down(slots[r]), want[r][0], f"sum r={r}")
+        else:
+            assert_bits_equal(down(slots[r], mode), want[r][0], f"payload r={r}")
+    ov.close()
+    rt.close()
+
+
+def test_allreduce_pipelined_rejects_bad_arguments():
     n = 4096 * 4
     g = [dev_zeros(n) for _ in range(2)]
     slots = [pay_buf(B.TRUNC16, n) for _ in range(2)]
     recv = [pay_buf(B.TRUNC16, n) for _ in range(2)]
     ov = B.Overlap()
-    ring = B.make_ring(B.TRUNC16, n, g, slots, None, [(0, 8192), (8192, 8192)])
-    with pytest.raises(B.PipeSgdError):
-        B.allreduce_pipelined(ring, recv, None, 2, ov)
     ring = B.make_ring(B.TRUNC16, n, g, slots, None)
     with pytest.raises(B.PipeSgdError):
         B.allreduce_pipelined(ring, recv, None, 0, ov)
