@@ -612,6 +612,34 @@ def test_two_stream_runtime_matches_oracle(orc, mode, width):
     rt.close()
 
 
+@pytest.mark.parametrize("compute_us,wire_us", [(0.0, 0.0), (0.0, 400.0), (400.0, 0.0), (60.0, 500.0), (500.0, 60.0)])
+@pytest.mark.parametrize("width", [2, 3])
+def test_two_stream_runtime_is_insensitive_to_timing(orc, compute_us, wire_us, width):
+    # whichever stream runs ahead, the ready marks must order every read after the write it needs:
+    # the result never depends on how long the compute stand-in or the network stand-in takes.
+    # The gradients are double-buffered here so that the host never has to wait between iterations.
+    mode, p, n, lr, m, iters = B.TRUNC16, 4, 4096 * 7 + 99, 0.02, 0.9, 10
+    grad_fn = lambda r, w, t: W.gaussian(n, 1e-3, 27, (width, r, t, 0))
+    w0 = W.gaussian(n, 0.05, 29)
+    K = max(width, 2)
+    sim = PipeSgdSim(mode, p, n, lr, m, 1.0, K)
+    sim.set_model(w0)
+    g_sets = [[up(grad_fn(r, None, t)) for r in range(p)] for t in range(1, iters + 1)]   # one set per iteration
+    rings = [[B.make_ring(mode, n, g_sets[t], sim.slots[i], None) for i in range(K)] for t in range(iters)]
+    sync()
+    rt = B.Runtime()
+    for t in range(1, iters + 1):
+        cur = t % K
+        rt.iteration(rings[t - 1][cur], sim.updates[(cur + 1) % K], sim.updates[cur], B.STEPWISE, width, lr, m, 1.0,
+                     compute_us=compute_us, compute_workgroups=4, wire_us=wire_us)
+    rt.sync()
+    ws, vs = orc.pipe_sgd_run(mode, grad_fn, w0, p, iters, lr, m, 1.0, width)
+    for r in range(p):
+        assert_fp32_close_then_exact(sim.model(r), ws[r], f"w r={r}")
+        assert_fp32_close_then_exact(sim.velocity(r), vs[r], f"v r={r}")
+    rt.close()
+
+
 def test_runtime_rejects_widths_it_has_no_events_for():
     sim = PipeSgdSim(B.NONE, 2, 4096 * 2, 0.01, 0.0, 1.0, 2)
     rt = B.Runtime()
