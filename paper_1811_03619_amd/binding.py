@@ -295,7 +295,7 @@ def allreduce_sim(ring: RingStruct, schedule: int = STEPWISE, stream=None) -> No
 
 
 def allreduce_direct(ring: RingStruct, stage: Sequence, stage_scales: Optional[Sequence], stream=None) -> None:
-    check(lib().pipesgd_allreduce_direct(C.byref(ring), _ptr_array(stage),
+    check(lib().pipesgd_allreduce_direct(C.byref(ring), _ptr_array(stage) if stage is not None else None,
                                          _ptr_array(stage_scales) if stage_scales is not None else None,
                                          _stream(stream)), "pipesgd_allreduce_direct")
 
@@ -332,7 +332,7 @@ class Overlap:
 def allreduce_pipelined(ring: RingStruct, recv: Sequence, recv_scales: Optional[Sequence], segments: int,
                         overlap: Overlap, compute_stream=None, wire_stream=None, wire_workgroups: int = 0,
                         link_us_per_mib: float = 0.0) -> None:
-    check(lib().pipesgd_allreduce_pipelined(C.byref(ring), _ptr_array(recv),
+    check(lib().pipesgd_allreduce_pipelined(C.byref(ring), _ptr_array(recv) if recv is not None else None,
                                             _ptr_array(recv_scales) if recv_scales is not None else None,
                                             segments, wire_workgroups, link_us_per_mib, overlap.handle,
                                             _stream(compute_stream), _stream(wire_stream)),
