@@ -416,9 +416,10 @@ def study_within_allreduce(sim, B, torch, np, mode, n, n_true, p, reps: int = 15
             ts.append((_time.perf_counter() - t0) / reps * 1e3)
         return float(np.median(ts))
 
+    ws = B.make_workspace(recv, recv_sc)
+
     def pipelined(seg, two_streams, **kw):
-        return timed(lambda: B.allreduce_pipelined(ring, recv, recv_sc, seg, ov, comp, wire if two_streams else comp,
-                                                   **kw))
+        return timed(lambda: B.allreduce_pipelined(ring, ws, seg, ov, comp, wire if two_streams else comp, **kw))
 
     res = {"study": "within-allreduce", "unit": "ms", "timing": "wall clock over back-to-back calls"}
     res["in_place_stepwise"] = round(timed(lambda: B.allreduce_sim(ring, B.STEPWISE, comp)), 5)

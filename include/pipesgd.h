@@ -55,8 +55,8 @@ extern "C" {
 #define PIPESGD_MAX_BUCKETS  64
 #define PIPESGD_QBLOCK       4096     /* elements per quantisation block and per tile */
 
-/* compression modes (Sec. 3.2; widths from Sec. 4 "Results and Analysis":
- * 16-bit truncation "T", 8-bit quantisation "Q") */
+/* compression modes (Sec. 3.2; widths from the results part of Sec. 4:
+ * truncation to 16 bits, there called T, and quantisation to 8 bits, Q) */
 #define PIPESGD_NONE     0
 #define PIPESGD_TRUNC16  1
 #define PIPESGD_QUANT8   2
@@ -69,7 +69,8 @@ extern "C" {
 #define PIPESGD_ERR_ARG       -1   /* null pointer, count or index out of range */
 #define PIPESGD_ERR_ALIGN     -2   /* a DEVICE pointer is not 16-byte aligned, or a bucket start is not a multiple of 4096 */
 #define PIPESGD_ERR_MODE      -3   /* unknown compression mode or schedule */
-#define PIPESGD_ERR_CAPACITY  -4   /* more workers or buckets than the library supports, or output table too small */
+#define PIPESGD_ERR_CAPACITY  -4   /* more workers, buckets or sub-blocks than the library supports; an output
+                                      table or a workspace buffer too small */
 #define PIPESGD_ERR_HIP       -5   /* the HIP runtime refused the launch */
 
 const char *pipesgd_strerror(int err);
@@ -78,8 +79,8 @@ int pipesgd_version(void);
 /* ------------------------------------------------------------------ sizes -- */
 
 /* Length of one ring block: ceil(n/p) rounded up to a multiple of 4096, so that
- * no quantisation block straddles two ring blocks ("a block of the entire
- * gradient vector", Sec. 3.1; n/p in Eq. 5).  0 if p < 1. */
+ * no quantisation block straddles two ring blocks (Sec. 3.1 splits the gradient
+ * vector into one block per worker; n/p in Eq. 5).  0 if p < 1. */
 uint64_t pipesgd_chunk_elems(uint64_t n, int workers);
 /* Bytes of a payload of n elements, scales not included; 0 for a bad mode. */
 uint64_t pipesgd_payload_bytes(int mode, uint64_t n);
@@ -161,20 +162,53 @@ int pipesgd_ring_allgather_step(const pipesgd_ring *ring, int step, void *stream
  * bytes moved, for launch-bound (small or many-bucket) gradients. */
 int pipesgd_allreduce_sim(const pipesgd_ring *ring, int schedule, void *stream);
 
+/* Scratch that a schedule needs PER WORKER beyond the gradients and the result
+ * slots; the caller allocates it (the library allocates nothing) and passes it
+ * in a pipesgd_workspace.  HOST arithmetic.
+ *   bytes[0]  payload-sized staging (stage), = pipesgd_payload_bytes(mode, n)
+ *   bytes[1]  its per-block scales (stage_scales), QUANT8 only
+ *   bytes[2]  fp32 partial sums (partial), halving-doubling with more than two workers
+ * all zero for the ring schedules of pipesgd_allreduce_sim and for one worker.
+ * Returns PIPESGD_ERR_MODE for an unknown mode or schedule, PIPESGD_ERR_ARG for
+ * workers < 1 or a NULL table. */
+#define PIPESGD_WS_RING              0   /* pipesgd_allreduce_sim, both schedules, and pipesgd_iteration_fused */
+#define PIPESGD_WS_PIPELINED         1   /* pipesgd_allreduce_pipelined */
+#define PIPESGD_WS_DIRECT            2   /* pipesgd_allreduce_direct */
+#define PIPESGD_WS_HALVING_DOUBLING  3   /* pipesgd_allreduce_halving_doubling */
+int pipesgd_workspace_bytes(int schedule, int mode, uint64_t n, int workers, uint64_t bytes[3]);
+
+/* The scratch itself, as the three schedules above take it.  Plain data, HOST
+ * struct; the three tables are HOST arrays of ring->workers DEVICE pointers.
+ * Each *_bytes field is the size of EVERY buffer in its table; an entry point
+ * returns PIPESGD_ERR_CAPACITY when a size it needs is below what
+ * pipesgd_workspace_bytes states for (its schedule, ring->mode, ring->n,
+ * ring->workers), PIPESGD_ERR_ARG / PIPESGD_ERR_ALIGN for a missing or
+ * misaligned buffer it needs.  Tables and sizes a schedule or mode does not need
+ * are ignored (stage_scales unless QUANT8; partial unless halving-doubling with
+ * p > 2).  Contents are scratch: undefined after the call, nothing expected
+ * before it. */
+typedef struct pipesgd_workspace {
+    void  *const *stage;           /* payload staging: receive buffers (pipelined) / send buffers */
+    float *const *stage_scales;
+    float *const *partial;
+    uint64_t stage_bytes;
+    uint64_t stage_scales_bytes;
+    uint64_t partial_bytes;
+} pipesgd_workspace;
+
 /* A second AllReduce schedule, the one-exchange ("direct") schedule -- what an
  * 8-GPU node with a direct link between every pair of GPUs would run instead
  * of a ring (Sec. 3.1 notes that its analysis carries over to other AllReduce
  * algorithms).  Worker j owns chunk j.  Exchange 1: every worker k compresses
- * chunk j of its gradient for every j != k (into stage[k], its send buffer).
+ * chunk j of its gradient for every j != k (into ws->stage[k], its send buffer).
  * Owner j then computes  P = g_j[j];  P = P + D(stage[(j+d) mod p][j]) for
  * d = 1..p-1 in this order;  and, exchange 2, writes C(P) into all p result
  * slots.  Two launches, two exchanges instead of 2(p-1), the same volume on the
  * links, and every value passes the codec twice instead of p times (less loss
  * than the ring; with PIPESGD_NONE the result bits equal the ring's).
- * stage / stage_scales: HOST arrays of p DEVICE buffers, each as large as a
- * result slot; contents are scratch.  Buckets are supported. */
-int pipesgd_allreduce_direct(const pipesgd_ring *ring, void *const *stage, float *const *stage_scales,
-                             void *stream);
+ * ws: stage (and stage_scales with QUANT8), sized as PIPESGD_WS_DIRECT says; may
+ * be NULL for one worker or an empty vector.  Buckets are supported. */
+int pipesgd_allreduce_direct(const pipesgd_ring *ring, const pipesgd_workspace *ws, void *stream);
 
 /* A third AllReduce schedule: recursive halving and doubling, one of the
  * algorithms Sec. 3.1's closing remark names beside the ring (reduce-scatter by
@@ -194,12 +228,10 @@ int pipesgd_allreduce_direct(const pipesgd_ring *ring, void *const *stage, float
  * 1 + log2(p) + log2(p) launches (one less without compression): a halving
  * round also compresses, in the same pass, the part of its sums that is sent
  * in the next round.
- * stage / stage_scales: HOST arrays of p DEVICE send buffers, each as large as
- * a result slot.  partial: HOST array of p DEVICE float buffers of ring->n
- * elements (the partial sums; needed when p > 2, may be NULL otherwise).
- * Contents of all three are scratch.  Buckets are supported. */
-int pipesgd_allreduce_halving_doubling(const pipesgd_ring *ring, void *const *stage, float *const *stage_scales,
-                                       float *const *partial, void *stream);
+ * ws: stage = the p send buffers (stage_scales with QUANT8), partial = the fp32
+ * partial sums (needed when p > 2), sized as PIPESGD_WS_HALVING_DOUBLING says.
+ * Buckets are supported. */
+int pipesgd_allreduce_halving_doubling(const pipesgd_ring *ring, const pipesgd_workspace *ws, void *stream);
 
 /* Placement advice, HOST arithmetic.  MI355X interleaves its HBM channels within
  * 4 KiB; allocators hand out large buffers at multiples of 2 MiB, so the streams
@@ -224,20 +256,6 @@ int pipesgd_allreduce_halving_doubling(const pipesgd_ring *ring, void *const *st
 #define PIPESGD_BUF_PARTIAL   9
 uint64_t pipesgd_placement_offset(int kind, int worker, int workers);
 
-/* Scratch that a schedule needs PER WORKER beyond the gradients and the result
- * slots; the caller allocates it (the library allocates nothing) and passes it
- * as the staging arguments of the entry point named below.  HOST arithmetic.
- *   bytes[0]  payload-sized staging (recv / stage), = pipesgd_payload_bytes(mode, n)
- *   bytes[1]  its per-block scales (recv_scales / stage_scales), QUANT8 only
- *   bytes[2]  fp32 partial sums (partial), halving-doubling with more than two workers
- * all zero for the ring schedules of pipesgd_allreduce_sim and for one worker.
- * Returns PIPESGD_ERR_MODE for an unknown mode or schedule, PIPESGD_ERR_ARG for
- * workers < 1 or a NULL table. */
-#define PIPESGD_WS_RING              0   /* pipesgd_allreduce_sim, both schedules, and pipesgd_iteration_fused */
-#define PIPESGD_WS_PIPELINED         1   /* pipesgd_allreduce_pipelined */
-#define PIPESGD_WS_DIRECT            2   /* pipesgd_allreduce_direct */
-#define PIPESGD_WS_HALVING_DOUBLING  3   /* pipesgd_allreduce_halving_doubling */
-int pipesgd_workspace_bytes(int schedule, int mode, uint64_t n, int workers, uint64_t bytes[3]);
 
 /* ---------------------------------------- pipelining within the AllReduce -- */
 
@@ -248,7 +266,7 @@ int  pipesgd_overlap_create(pipesgd_overlap **out);
 void pipesgd_overlap_destroy(pipesgd_overlap *ov);
 
 /* The AllReduce as a two-stage pipeline over `segments` sub-blocks of every
- * ring block (Sec. 3.2, "pipelining within AllReduce", Fig. 3(b)): stage 1,
+ * ring block (Sec. 3.2's pipelining inside the AllReduce, Fig. 3(b)): stage 1,
  * the compressed communication, copies a sub-block of the sender's payload into
  * the receiver's staging buffer recv[r] on `wire_stream`; stage 2, (decompress,
  * sum, compress), runs on `compute_stream` on what has arrived, while the next
@@ -257,8 +275,9 @@ void pipesgd_overlap_destroy(pipesgd_overlap *ov);
  * a receiver reads the sender's buffer in place, every hop payload here is
  * moved once more (the stand-in for the wire), so this costs bandwidth on one
  * GPU; it exists to measure how much of the codec time the transfer hides.
- * recv / recv_scales: HOST arrays of p DEVICE buffers, each as large as a result
- * slot (payload of n elements / its scales); contents are scratch.
+ * ws: stage = the p receive buffers recv[r] (stage_scales with QUANT8), sized
+ * as PIPESGD_WS_PIPELINED says.  1 <= segments <= PIPESGD_MAX_SEGMENTS
+ * (PIPESGD_ERR_CAPACITY above).
  * Buckets are supported (a sub-block is a range of the ring block's tiles, counted
  * across buckets).  On return both streams hold work; compute_stream
  * is made to wait for the end of it, and wire_stream for everything enqueued on
@@ -272,8 +291,10 @@ void pipesgd_overlap_destroy(pipesgd_overlap *ov);
  * buffer the wire stream idles for x microseconds per MiB that one worker sends
  * in it (one wavefront, no memory traffic): the time the bytes spend on a network
  * of 1/x MiB/us -- Eq. 5's beta -- which, unlike a copy inside one HBM, competes
- * with nothing, so stage 2 of the previous sub-block runs beside it. */
-int pipesgd_allreduce_pipelined(const pipesgd_ring *ring, void *const *recv, float *const *recv_scales,
+ * with nothing, so stage 2 of the previous sub-block runs beside it.  The delay
+ * of one whole ring block may not pass one second (PIPESGD_ERR_ARG). */
+#define PIPESGD_MAX_SEGMENTS 64
+int pipesgd_allreduce_pipelined(const pipesgd_ring *ring, const pipesgd_workspace *ws,
                                 int segments, int wire_workgroups, float link_us_per_mib, pipesgd_overlap *ov,
                                 void *compute_stream, void *wire_stream);
 
@@ -370,7 +391,11 @@ int pipesgd_unpack(const pipesgd_segment *segments, uint64_t num, uint64_t total
  * t-(K-1) (an all-zero set while t < K), `fresh_*` the set `ring` writes (width
  * 1 only).
  * The caller must not change g_local while an AllReduce that reads it may still
- * be running (pipesgd_runtime_sync, or double-buffer the gradients). */
+ * be running (pipesgd_runtime_sync, or double-buffer the gradients).
+ * pipesgd_runtime_iteration checks every field (the ring, the slot / w / v tables
+ * of the update it will launch, both durations) before its first launch or event
+ * record: after an error other than PIPESGD_ERR_HIP the runtime is as it was and
+ * the same iteration can be issued again. */
 typedef struct pipesgd_runtime pipesgd_runtime;
 
 typedef struct pipesgd_runtime_iter {
@@ -378,7 +403,7 @@ typedef struct pipesgd_runtime_iter {
     int32_t  schedule;                   /* PIPESGD_STEPWISE / PIPESGD_FUSED */
     int32_t  width;                      /* 2 = pipelined (staleness 1), 1 = synchronous, 3..7 = staleness width-1 */
     int32_t  replicas;                   /* model replicas to update (normally ring->workers) */
-    int32_t  compute_workgroups;         /* workgroups the compute stand-in occupies (>= 1) */
+    int32_t  compute_workgroups;         /* workgroups the compute stand-in occupies (1..65535; below 1 is taken as 1) */
     float    compute_us;                 /* duration of the compute stand-in, microseconds (0 = none) */
     float    wire_us;                    /* extra delay on the comm stream after the AllReduce kernels: the time
                                             the payloads would spend on a network (Eq. 5's alpha and beta terms);
@@ -433,9 +458,10 @@ double pipesgd_model_scaling_efficiency(double l_up, double l_comp, double l_com
  * (512,1) (512,2) (1024,1); QUANT8 kernels that compute a block's range need
  * threads*quads == 1024; the all-gather copy needs threads*quads*16 bytes to
  * divide a tile's payload.  0 <= lds_bytes <= 162816 (159 KiB).
- * The table is process-global and not synchronised: set it before launching
- * from several threads.  Returns PIPESGD_ERR_ARG for an unsupported combination
- * (the table is left unchanged).  Results never depend on it. */
+ * The table is process-global; each entry is read and written as one atomic
+ * word, so a launch concurrent with a change uses the old or the new geometry.
+ * Returns PIPESGD_ERR_ARG for an unsupported combination (the table is left
+ * unchanged).  Results never depend on it. */
 #define PIPESGD_K_FIRST_SEND      0
 #define PIPESGD_K_REDUCE_SCATTER  1
 #define PIPESGD_K_ALLGATHER       2

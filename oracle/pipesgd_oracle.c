@@ -9,7 +9,7 @@
  * What it follows (arXiv 1811.03619):
  *   - Sec. 3.1, Ring-AllReduce paragraph + Fig. 2(c): every worker transmits
  *     one block of the gradient to its ring neighbour and sum-reduces the
- *     block it receives ("transmit-and-reduce", p-1 rounds), until each block
+ *     block it receives (p-1 rounds of transmitting and reducing), until each block
  *     is fully reduced on a different worker; the reduced blocks then travel
  *     round the ring to the other workers (p-1 more rounds).  Cost terms of
  *     Eq. 5: 2(p-1) rounds, 2((p-1)/p)n bytes sent, ((p-1)/p)n bytes reduced.
@@ -56,8 +56,8 @@ enum { ORC_NONE = 0, ORC_TRUNC16 = 1, ORC_QUANT8 = 2 };
 
 /* Block ("chunk") length used to split an n-element vector over p workers:
  * ceil(n/p) rounded up to a whole number of quantization blocks, so that no
- * quantization block straddles two ring blocks.  (Sec. 3.1: "a block of the
- * entire gradient vector"; n/p in Eq. 5.) */
+ * quantization block straddles two ring blocks.  (Sec. 3.1 gives every worker
+ * one block of the gradient vector; n/p in Eq. 5.) */
 size_t orc_chunk_elems(size_t n, int p)
 {
     size_t per = (n + (size_t)p - 1) / (size_t)p;

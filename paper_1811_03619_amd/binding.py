@@ -73,6 +73,11 @@ class RuntimeIter(C.Structure):
     ]
 
 
+class Workspace(C.Structure):
+    _fields_ = [("stage", C.c_void_p), ("stage_scales", C.c_void_p), ("partial", C.c_void_p),
+                ("stage_bytes", C.c_uint64), ("stage_scales_bytes", C.c_uint64), ("partial_bytes", C.c_uint64)]
+
+
 class Segment(C.Structure):
     _fields_ = [("tensor", C.c_void_p), ("packed", C.c_void_p), ("numel", C.c_uint64),
                 ("first_tile", C.c_uint64)]
@@ -136,7 +141,7 @@ def lib():
     L.pipesgd_overlap_destroy.restype = None
     L.pipesgd_overlap_destroy.argtypes = [vp]
     L.pipesgd_allreduce_pipelined.restype = i32
-    L.pipesgd_allreduce_pipelined.argtypes = [C.POINTER(RingStruct), vp, vp, i32, i32, f32, vp, vp, vp]
+    L.pipesgd_allreduce_pipelined.argtypes = [C.POINTER(RingStruct), C.POINTER(Workspace), i32, i32, f32, vp, vp, vp]
     L.pipesgd_runtime_create.restype = i32
     L.pipesgd_runtime_create.argtypes = [C.POINTER(vp)]
     L.pipesgd_runtime_destroy.restype = None
@@ -157,13 +162,13 @@ def lib():
     L.pipesgd_model_ring_comm_time.restype = dbl
     L.pipesgd_model_ring_comm_time.argtypes = [i32, dbl, dbl, dbl, dbl, dbl, i32]
     L.pipesgd_allreduce_direct.restype = i32
-    L.pipesgd_allreduce_direct.argtypes = [C.POINTER(RingStruct), vp, vp, vp]
+    L.pipesgd_allreduce_direct.argtypes = [C.POINTER(RingStruct), C.POINTER(Workspace), vp]
     L.pipesgd_placement_offset.restype = u64
     L.pipesgd_placement_offset.argtypes = [i32, i32, i32]
     L.pipesgd_workspace_bytes.restype = i32
     L.pipesgd_workspace_bytes.argtypes = [i32, i32, u64, i32, C.POINTER(C.c_uint64)]
     L.pipesgd_allreduce_halving_doubling.restype = i32
-    L.pipesgd_allreduce_halving_doubling.argtypes = [C.POINTER(RingStruct), vp, vp, vp, vp]
+    L.pipesgd_allreduce_halving_doubling.argtypes = [C.POINTER(RingStruct), C.POINTER(Workspace), vp]
     L.pipesgd_iteration_fused.restype = i32
     L.pipesgd_iteration_fused.argtypes = [C.POINTER(RingStruct), vp, vp, vp, vp, f32, f32, f32, vp]
     L.pipesgd_set_launch_config.restype = i32
@@ -294,18 +299,46 @@ def allreduce_sim(ring: RingStruct, schedule: int = STEPWISE, stream=None) -> No
     check(lib().pipesgd_allreduce_sim(C.byref(ring), schedule, _stream(stream)), "pipesgd_allreduce_sim")
 
 
-def allreduce_direct(ring: RingStruct, stage: Sequence, stage_scales: Optional[Sequence], stream=None) -> None:
-    check(lib().pipesgd_allreduce_direct(C.byref(ring), _ptr_array(stage) if stage is not None else None,
-                                         _ptr_array(stage_scales) if stage_scales is not None else None,
-                                         _stream(stream)), "pipesgd_allreduce_direct")
+def _nbytes(t) -> int:
+    """Bytes of a torch tensor; a raw address says nothing about its size."""
+    return t.numel() * t.element_size()
 
 
-def allreduce_halving_doubling(ring: RingStruct, stage: Sequence, stage_scales: Optional[Sequence],
-                               partial: Optional[Sequence], stream=None) -> None:
-    check(lib().pipesgd_allreduce_halving_doubling(C.byref(ring), _ptr_array(stage) if stage is not None else None,
-                                                   _ptr_array(stage_scales) if stage_scales is not None else None,
-                                                   _ptr_array(partial) if partial is not None else None,
-                                                   _stream(stream)),
+def make_workspace(stage: Optional[Sequence] = None, stage_scales: Optional[Sequence] = None,
+                   partial: Optional[Sequence] = None, sizes: Optional[Tuple[int, int, int]] = None) -> Workspace:
+    """Fill a pipesgd_workspace from lists of torch tensors (or raw addresses,
+    then `sizes` = bytes of each stage / stage_scales / partial buffer must be
+    given).  The returned struct keeps the pointer tables alive."""
+    ws = Workspace()
+    tabs = []
+    for name, items in (("stage", stage), ("stage_scales", stage_scales), ("partial", partial)):
+        if items is None:
+            setattr(ws, name, None)
+            tabs.append(None)
+        else:
+            arr = _ptr_array(items)
+            tabs.append(arr)
+            setattr(ws, name, C.cast(arr, C.c_void_p))
+    ws._keepalive = tabs
+    if sizes is None:
+        def smallest(items):
+            known = [_nbytes(t) for t in (items or []) if t is not None and not isinstance(t, int)]
+            return min(known) if known else 0
+        sizes = (smallest(stage), smallest(stage_scales), smallest(partial))
+    ws.stage_bytes, ws.stage_scales_bytes, ws.partial_bytes = (int(x) for x in sizes)
+    return ws
+
+
+def _ws_arg(ws: Optional[Workspace]):
+    return C.byref(ws) if ws is not None else None
+
+
+def allreduce_direct(ring: RingStruct, ws: Optional[Workspace], stream=None) -> None:
+    check(lib().pipesgd_allreduce_direct(C.byref(ring), _ws_arg(ws), _stream(stream)), "pipesgd_allreduce_direct")
+
+
+def allreduce_halving_doubling(ring: RingStruct, ws: Optional[Workspace], stream=None) -> None:
+    check(lib().pipesgd_allreduce_halving_doubling(C.byref(ring), _ws_arg(ws), _stream(stream)),
           "pipesgd_allreduce_halving_doubling")
 
 
@@ -329,13 +362,11 @@ class Overlap:
             pass
 
 
-def allreduce_pipelined(ring: RingStruct, recv: Sequence, recv_scales: Optional[Sequence], segments: int,
+def allreduce_pipelined(ring: RingStruct, ws: Optional[Workspace], segments: int,
                         overlap: Overlap, compute_stream=None, wire_stream=None, wire_workgroups: int = 0,
                         link_us_per_mib: float = 0.0) -> None:
-    check(lib().pipesgd_allreduce_pipelined(C.byref(ring), _ptr_array(recv) if recv is not None else None,
-                                            _ptr_array(recv_scales) if recv_scales is not None else None,
-                                            segments, wire_workgroups, link_us_per_mib, overlap.handle,
-                                            _stream(compute_stream), _stream(wire_stream)),
+    check(lib().pipesgd_allreduce_pipelined(C.byref(ring), _ws_arg(ws), segments, wire_workgroups, link_us_per_mib,
+                                            overlap.handle, _stream(compute_stream), _stream(wire_stream)),
           "pipesgd_allreduce_pipelined")
 
 

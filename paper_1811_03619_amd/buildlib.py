@@ -15,7 +15,7 @@ INCLUDE = os.path.join(ROOT, "include")
 LIB_PATH = os.path.join(_HERE, "libpipesgd.so")
 
 SOURCES = ["pipesgd_kernels.hip", "pipesgd_runtime.hip", "pipesgd_host.cpp"]
-HEADERS = ["pipesgd_device.hpp"]                      # private to csrc/; included by pipesgd_kernels.hip
+HEADERS = ["pipesgd_device.hpp", "pipesgd_internal.hpp"]      # private to csrc/
 
 # One IEEE rounding per written operation: no contraction, no fast-math.
 # Packed-fp32 instruction selection is switched off on purpose.

@@ -16,7 +16,7 @@ const char *pipesgd_strerror(int err)
     case PIPESGD_ERR_ARG:      return "invalid argument (null pointer, or a count/index out of range)";
     case PIPESGD_ERR_ALIGN:    return "device pointer not 16-byte aligned, or bucket start not a multiple of 4096";
     case PIPESGD_ERR_MODE:     return "unknown compression mode or schedule";
-    case PIPESGD_ERR_CAPACITY: return "too many workers or buckets, or output table too small";
+    case PIPESGD_ERR_CAPACITY: return "too many workers, buckets or sub-blocks, or an output table or workspace buffer too small";
     case PIPESGD_ERR_HIP:      return "HIP runtime error at kernel launch";
     default:                   return "unknown pipesgd error";
     }

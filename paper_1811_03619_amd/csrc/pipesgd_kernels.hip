@@ -31,6 +31,7 @@
 #include <vector>
 
 #include "pipesgd.h"
+#include "pipesgd_internal.hpp"
 
 #pragma clang fp contract(off)
 
@@ -438,15 +439,27 @@ struct LaunchConfig {
 // interleave).  The update is fastest with about 24-30 KiB of loads in flight per
 // compute unit: small workgroups and an LDS reservation that admits two or three
 // of them per CU.  The hop kernels are nearly flat across geometries.  [kind][mode]
-LaunchConfig g_cfg[kNumKinds][3] = {
-    /* first send     */ {{256, 4, 0}, {128, 2, 0}, {512, 2, 32768}},
-    /* reduce-scatter */ {{128, 2, 0}, {128, 2, 0}, {256, 4, 32768}},
-    /* all-gather     */ {{128, 2, 0}, {256, 2, 0}, {256, 1, 0}},
-    /* fused          */ {{256, 1, 0}, {256, 1, 0}, {256, 4, 0}},
-    /* update         */ {{256, 1, 65536}, {64, 4, 53248}, {64, 4, 53248}},
-    /* compress       */ {{256, 4, 0}, {512, 2, 0}, {512, 2, 0}},
-    /* decompress     */ {{256, 4, 0}, {256, 2, 0}, {128, 2, 0}},
+// Each entry is one atomic word, so a launch that reads it while another thread
+// calls pipesgd_set_launch_config uses the old or the new geometry, never a
+// mixture of the two.
+constexpr uint64_t pack_cfg(int threads, int quads, int lds_bytes)
+{
+    return static_cast<uint64_t>(threads) | (static_cast<uint64_t>(quads) << 16) | (static_cast<uint64_t>(lds_bytes) << 32);
+}
+std::atomic<uint64_t> g_cfg[kNumKinds][3] = {
+    /* first send     */ {pack_cfg(256, 4, 0), pack_cfg(128, 2, 0), pack_cfg(512, 2, 32768)},
+    /* reduce-scatter */ {pack_cfg(128, 2, 0), pack_cfg(128, 2, 0), pack_cfg(256, 4, 32768)},
+    /* all-gather     */ {pack_cfg(128, 2, 0), pack_cfg(256, 2, 0), pack_cfg(256, 1, 0)},
+    /* fused          */ {pack_cfg(256, 1, 0), pack_cfg(256, 1, 0), pack_cfg(256, 4, 0)},
+    /* update         */ {pack_cfg(256, 1, 65536), pack_cfg(64, 4, 53248), pack_cfg(64, 4, 53248)},
+    /* compress       */ {pack_cfg(256, 4, 0), pack_cfg(512, 2, 0), pack_cfg(512, 2, 0)},
+    /* decompress     */ {pack_cfg(256, 4, 0), pack_cfg(256, 2, 0), pack_cfg(128, 2, 0)},
 };
+inline LaunchConfig cfg_of(int kind, int mode)
+{
+    const uint64_t v = g_cfg[kind][mode].load(std::memory_order_relaxed);
+    return LaunchConfig{static_cast<int>(v & 0xffff), static_cast<int>((v >> 16) & 0xffff), static_cast<int>(v >> 32)};
+}
 
 constexpr int kMaxLds = 159 * 1024;        // a CU has 160 KiB; leave room for the kernels' own few bytes
 
@@ -515,22 +528,23 @@ int prepare_ring(const pipesgd_ring *ring, RingArgs &ra, BucketTable &bt, uint64
     for (int r = 0; r < kMaxW; ++r) {
         ra.g[r] = nullptr; ra.in[r] = nullptr; ra.in_sc[r] = nullptr; ra.out[r] = nullptr; ra.out_sc[r] = nullptr;
     }
+    const bool q8 = ring->mode == PIPESGD_QUANT8;         // scales[] is read in this mode only
     for (int r = 0; r < p; ++r) {
         if (ring->n > 0) {
             if (!ring->g_local[r] || !ring->g_sum_c[r]) return PIPESGD_ERR_ARG;
-            if (ring->mode == PIPESGD_QUANT8 && !ring->scales[r]) return PIPESGD_ERR_ARG;
+            if (q8 && !ring->scales[r]) return PIPESGD_ERR_ARG;
         }
-        if (!aligned16(ring->g_local[r]) || !aligned16(ring->g_sum_c[r]) || !aligned16(ring->scales[r]))
+        if (!aligned16(ring->g_local[r]) || !aligned16(ring->g_sum_c[r]) || (q8 && !aligned16(ring->scales[r])))
             return PIPESGD_ERR_ALIGN;
         ra.g[r] = ring->g_local[r];
         ra.out[r] = ring->g_sum_c[r];
-        ra.out_sc[r] = ring->scales[r];
+        ra.out_sc[r] = q8 ? ring->scales[r] : nullptr;
     }
     // default wiring: worker r receives what worker r-1 holds in its slot
     for (int r = 0; r < p; ++r) {
         const int src = (r + p - 1) % p;
         ra.in[r] = ring->g_sum_c[src];
-        ra.in_sc[r] = ring->scales[src];
+        ra.in_sc[r] = q8 ? ring->scales[src] : nullptr;
     }
     ra.p = p;
     ra.chunk_rot = 0;
@@ -561,6 +575,42 @@ int prepare_ring(const pipesgd_ring *ring, RingArgs &ra, BucketTable &bt, uint64
     bt.slot_prefix[kMaxB] = static_cast<uint32_t>(slots);
     bt.count = nb;
     total_slots = slots;
+    return PIPESGD_OK;
+}
+
+// Staging a schedule needs, checked against what the caller says it has
+// allocated.  `kind` is a PIPESGD_WS_* schedule.  On success stage / stage_sc /
+// partial hold the p buffers (nullptr where the schedule and mode need none).
+struct Staging {
+    void *stage[kMaxW];
+    float *stage_sc[kMaxW];
+    float *partial[kMaxW];
+};
+int check_workspace(const pipesgd_ring *ring, const pipesgd_workspace *ws, int kind, Staging &st)
+{
+    for (int r = 0; r < kMaxW; ++r) { st.stage[r] = nullptr; st.stage_sc[r] = nullptr; st.partial[r] = nullptr; }
+    uint64_t need[3];
+    const int rc = pipesgd_workspace_bytes(kind, ring->mode, ring->n, ring->workers, need);
+    if (rc != PIPESGD_OK) return rc;
+    if (need[0] == 0 && need[1] == 0 && need[2] == 0) return PIPESGD_OK;      // one worker or an empty vector
+    if (!ws) return PIPESGD_ERR_ARG;
+    const int p = ring->workers;
+    if ((need[0] && !ws->stage) || (need[1] && !ws->stage_scales) || (need[2] && !ws->partial)) return PIPESGD_ERR_ARG;
+    for (int r = 0; r < p; ++r) {
+        if ((need[0] && !ws->stage[r]) || (need[1] && !ws->stage_scales[r]) || (need[2] && !ws->partial[r]))
+            return PIPESGD_ERR_ARG;
+        if ((need[0] && !aligned16(ws->stage[r])) || (need[1] && !aligned16(ws->stage_scales[r])) ||
+            (need[2] && !aligned16(ws->partial[r])))
+            return PIPESGD_ERR_ALIGN;
+    }
+    if (ws->stage_bytes < need[0] || (need[1] && ws->stage_scales_bytes < need[1]) ||
+        (need[2] && ws->partial_bytes < need[2]))
+        return PIPESGD_ERR_CAPACITY;
+    for (int r = 0; r < p; ++r) {
+        st.stage[r] = ws->stage[r];
+        st.stage_sc[r] = need[1] ? ws->stage_scales[r] : nullptr;
+        st.partial[r] = need[2] ? ws->partial[r] : nullptr;
+    }
     return PIPESGD_OK;
 }
 
@@ -728,7 +778,7 @@ int first_send_impl(int mode, RingArgs ra, const BucketTable &bt, uint64_t slots
 {
     // uncompressed, p > 1: the first round reads the sender's gradient in place
     if (slots == 0 || (mode == PIPESGD_NONE && ra.p > 1)) return PIPESGD_OK;
-    const LaunchConfig c = g_cfg[kFirstSend][mode];
+    const LaunchConfig c = cfg_of(kFirstSend, mode);
     ra.chunk_rot = 0;
 #define CALL(M) return launch_hop<M, false>(c, ra, bt, slots, 1, s);
     PIPESGD_MODE_SWITCH(mode, CALL)
@@ -740,7 +790,7 @@ int first_send_impl(int mode, RingArgs ra, const BucketTable &bt, uint64_t slots
 // caller (receive staging); otherwise it is read from the sender's buffers.
 int rs_impl(int mode, RingArgs ra, const BucketTable &bt, uint64_t slots, int step, bool staged, hipStream_t s)
 {
-    const LaunchConfig c = g_cfg[kReduceScatter][mode];
+    const LaunchConfig c = cfg_of(kReduceScatter, mode);
     ra.chunk_rot = step + 1;
     if (!staged && mode == PIPESGD_NONE && step == 0)
         for (int r = 0; r < ra.p; ++r) ra.in[r] = ra.g[(r + ra.p - 1) % ra.p];
@@ -753,7 +803,7 @@ int rs_impl(int mode, RingArgs ra, const BucketTable &bt, uint64_t slots, int st
 // Copy chunk (r - rot) mod p from ra.in[r] to ra.out[r] for every worker.
 int copy_impl(int mode, RingArgs ra, const BucketTable &bt, uint64_t slots, int rot, uint32_t max_groups, hipStream_t s)
 {
-    const LaunchConfig c = g_cfg[kAllGather][mode];
+    const LaunchConfig c = cfg_of(kAllGather, mode);
     ra.chunk_rot = rot;
 #define CALL(M) return launch_copy<M>(c, ra, bt, slots, max_groups, s);
     PIPESGD_MODE_SWITCH(mode, CALL)
@@ -763,7 +813,7 @@ int copy_impl(int mode, RingArgs ra, const BucketTable &bt, uint64_t slots, int 
 
 int fused_impl(int mode, const RingArgs &ra, const BucketTable &bt, uint64_t slots, hipStream_t s)
 {
-    const LaunchConfig c = g_cfg[kFused][mode];
+    const LaunchConfig c = cfg_of(kFused, mode);
 #define CALL(M) return launch_fused<M>(c, ra, bt, slots, s);
     PIPESGD_MODE_SWITCH(mode, CALL)
 #undef CALL
@@ -782,7 +832,7 @@ int pipesgd_set_launch_config(int kernel, int mode, int threads, int quads, int 
     if (!mode_ok(mode)) return PIPESGD_ERR_MODE;
     const LaunchConfig c = {threads, quads, lds_bytes};
     if (!config_ok(kernel, mode, c)) return PIPESGD_ERR_ARG;
-    g_cfg[kernel][mode] = c;
+    g_cfg[kernel][mode].store(pack_cfg(threads, quads, lds_bytes), std::memory_order_relaxed);
     return PIPESGD_OK;
 }
 
@@ -790,9 +840,10 @@ int pipesgd_get_launch_config(int kernel, int mode, int *threads, int *quads, in
 {
     if (kernel < 0 || kernel >= kNumKinds || !threads || !quads || !lds_bytes) return PIPESGD_ERR_ARG;
     if (!mode_ok(mode)) return PIPESGD_ERR_MODE;
-    *threads = g_cfg[kernel][mode].threads;
-    *quads = g_cfg[kernel][mode].quads;
-    *lds_bytes = g_cfg[kernel][mode].lds_bytes;
+    const LaunchConfig c = cfg_of(kernel, mode);
+    *threads = c.threads;
+    *quads = c.quads;
+    *lds_bytes = c.lds_bytes;
     return PIPESGD_OK;
 }
 
@@ -802,7 +853,7 @@ int pipesgd_compress(int mode, const float *src, uint64_t n, void *payload, floa
     if (n == 0) return PIPESGD_OK;
     if (!src || !payload || (mode == PIPESGD_QUANT8 && !scales)) return PIPESGD_ERR_ARG;
     if (!aligned16(src) || !aligned16(payload) || (mode == PIPESGD_QUANT8 && !aligned16(scales))) return PIPESGD_ERR_ALIGN;
-    const LaunchConfig c = g_cfg[kCompress][mode];
+    const LaunchConfig c = cfg_of(kCompress, mode);
     hipStream_t s = static_cast<hipStream_t>(stream);
 #define CALL(M) return launch_compress<M>(c, src, n, payload, scales, s);
     PIPESGD_MODE_SWITCH(mode, CALL)
@@ -816,7 +867,7 @@ int pipesgd_decompress(int mode, const void *payload, const float *scales, uint6
     if (n == 0) return PIPESGD_OK;
     if (!dst || !payload || (mode == PIPESGD_QUANT8 && !scales)) return PIPESGD_ERR_ARG;
     if (!aligned16(dst) || !aligned16(payload) || (mode == PIPESGD_QUANT8 && !aligned16(scales))) return PIPESGD_ERR_ALIGN;
-    const LaunchConfig c = g_cfg[kDecompress][mode];
+    const LaunchConfig c = cfg_of(kDecompress, mode);
     hipStream_t s = static_cast<hipStream_t>(stream);
 #define CALL(M) return launch_decompress<M>(c, payload, scales, n, dst, s);
     PIPESGD_MODE_SWITCH(mode, CALL)
@@ -871,28 +922,18 @@ int pipesgd_allreduce_sim(const pipesgd_ring *ring, int schedule, void *stream)
 
 // ------------------------------------------------- the one-exchange schedule --
 
-int pipesgd_allreduce_direct(const pipesgd_ring *ring, void *const *stage, float *const *stage_scales, void *stream)
+// Both exchanges of the one-exchange schedule on validated arguments.
+static int direct_impl(int mode, const RingArgs &ra, const BucketTable &bt, uint64_t slots, const Staging &st, hipStream_t s)
 {
-    RingArgs ra; BucketTable bt; uint64_t slots = 0;
-    int rc = prepare_ring(ring, ra, bt, slots);
-    if (rc != PIPESGD_OK) return rc;
-    const int mode = ring->mode, p = ring->workers;
-    if (slots == 0) return PIPESGD_OK;
-    if (p > 1) {
-        if (!stage || (mode == PIPESGD_QUANT8 && !stage_scales)) return PIPESGD_ERR_ARG;
-        for (int r = 0; r < p; ++r) {
-            if (!stage[r] || (mode == PIPESGD_QUANT8 && !stage_scales[r])) return PIPESGD_ERR_ARG;
-            if (!aligned16(stage[r]) || (mode == PIPESGD_QUANT8 && !aligned16(stage_scales[r]))) return PIPESGD_ERR_ALIGN;
-        }
-    }
-    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int p = ra.p;
+    int rc = PIPESGD_OK;
     if (p > 1) {
         // exchange 1: worker k compresses every chunk it does not own into its send buffer
         // (chunks k-1, k-2, ..., k-(p-1) along gridDim.z)
         RingArgs sc = ra;
-        for (int r = 0; r < p; ++r) { sc.out[r] = stage[r]; sc.out_sc[r] = mode == PIPESGD_QUANT8 ? stage_scales[r] : nullptr; }
+        for (int r = 0; r < p; ++r) { sc.out[r] = st.stage[r]; sc.out_sc[r] = st.stage_sc[r]; }
         sc.chunk_rot = 1;
-        const LaunchConfig c = g_cfg[kFirstSend][mode];
+        const LaunchConfig c = cfg_of(kFirstSend, mode);
 #define CALL(M) rc = launch_hop<M, false>(c, sc, bt, slots, p - 1, s);
         PIPESGD_MODE_SWITCH(mode, CALL)
 #undef CALL
@@ -902,36 +943,45 @@ int pipesgd_allreduce_direct(const pipesgd_ring *ring, void *const *stage, float
     // (exchange 2) writes the result into every worker's slot
     RingArgs rd = ra;
     for (int r = 0; r < p; ++r) {
-        rd.in[r] = p > 1 ? stage[r] : nullptr;
-        rd.in_sc[r] = (p > 1 && mode == PIPESGD_QUANT8) ? stage_scales[r] : nullptr;
+        rd.in[r] = p > 1 ? st.stage[r] : nullptr;
+        rd.in_sc[r] = p > 1 ? st.stage_sc[r] : nullptr;
     }
-    const LaunchConfig c2 = g_cfg[kFused][mode];
+    const LaunchConfig c2 = cfg_of(kFused, mode);
 #define CALL(M) return launch_direct_reduce<M>(c2, rd, bt, slots, s);
     PIPESGD_MODE_SWITCH(mode, CALL)
 #undef CALL
     return PIPESGD_ERR_MODE;
 }
 
+int pipesgd_allreduce_direct(const pipesgd_ring *ring, const pipesgd_workspace *ws, void *stream)
+{
+    RingArgs ra; BucketTable bt; uint64_t slots = 0;
+    int rc = prepare_ring(ring, ra, bt, slots);
+    if (rc != PIPESGD_OK) return rc;
+    Staging st;
+    rc = check_workspace(ring, ws, PIPESGD_WS_DIRECT, st);
+    if (rc != PIPESGD_OK) return rc;
+    if (slots == 0) return PIPESGD_OK;
+    return direct_impl(ring->mode, ra, bt, slots, st, static_cast<hipStream_t>(stream));
+}
+
 // ------------------------------------------ recursive halving and doubling --
 
-int pipesgd_allreduce_halving_doubling(const pipesgd_ring *ring, void *const *stage, float *const *stage_scales,
-                                       float *const *partial, void *stream)
+int pipesgd_allreduce_halving_doubling(const pipesgd_ring *ring, const pipesgd_workspace *ws, void *stream)
 {
     RingArgs ra; BucketTable bt; uint64_t slots = 0;
     int rc = prepare_ring(ring, ra, bt, slots);
     if (rc != PIPESGD_OK) return rc;
     const int mode = ring->mode, p = ring->workers;
     if ((p & (p - 1)) != 0) return PIPESGD_ERR_ARG;
+    Staging st;
+    rc = check_workspace(ring, ws, PIPESGD_WS_HALVING_DOUBLING, st);
+    if (rc != PIPESGD_OK) return rc;
     if (slots == 0) return PIPESGD_OK;
     const bool q8 = mode == PIPESGD_QUANT8;
-    if (p > 1) {
-        if (!stage || (q8 && !stage_scales) || (p > 2 && !partial)) return PIPESGD_ERR_ARG;
-        for (int r = 0; r < p; ++r) {
-            if (!stage[r] || (q8 && !stage_scales[r]) || (p > 2 && !partial[r])) return PIPESGD_ERR_ARG;
-            if (!aligned16(stage[r]) || (q8 && !aligned16(stage_scales[r])) || (p > 2 && !aligned16(partial[r])))
-                return PIPESGD_ERR_ALIGN;
-        }
-    }
+    void *const *stage = st.stage;
+    float *const *stage_scales = st.stage_sc;
+    float *const *partial = st.partial;
     hipStream_t s = static_cast<hipStream_t>(stream);
     HdArgs ha;
     for (int r = 0; r < kMaxW; ++r) {
@@ -939,7 +989,7 @@ int pipesgd_allreduce_halving_doubling(const pipesgd_ring *ring, void *const *st
         ha.acc[r] = nullptr;
     }
     ha.half = 1; ha.flip = 0; ha.next_half = 0;
-    const LaunchConfig c_send = g_cfg[kFirstSend][mode], c_red = g_cfg[kReduceScatter][mode], c_copy = g_cfg[kAllGather][mode];
+    const LaunchConfig c_send = cfg_of(kFirstSend, mode), c_red = cfg_of(kReduceScatter, mode), c_copy = cfg_of(kAllGather, mode);
 
     if (p == 1) {                                        // nothing to exchange: the slot is C(g)
         ha.src[0] = ra.g[0]; ha.pay[0] = ra.out[0]; ha.pay_sc[0] = ra.out_sc[0];
@@ -1027,7 +1077,7 @@ static bool overlap_event(pipesgd_overlap *ov, size_t i, hipEvent_t *e)
     return true;
 }
 
-int pipesgd_allreduce_pipelined(const pipesgd_ring *ring, void *const *recv, float *const *recv_scales,
+int pipesgd_allreduce_pipelined(const pipesgd_ring *ring, const pipesgd_workspace *ws,
                                 int segments, int wire_workgroups, float link_us_per_mib, pipesgd_overlap *ov,
                                 void *compute_stream, void *wire_stream)
 {
@@ -1035,30 +1085,39 @@ int pipesgd_allreduce_pipelined(const pipesgd_ring *ring, void *const *recv, flo
     int rc = prepare_ring(ring, ra, bt, slots);
     if (rc != PIPESGD_OK) return rc;
     if (!ov || segments < 1 || wire_workgroups < 0 || !(link_us_per_mib >= 0.0f)) return PIPESGD_ERR_ARG;
+    if (segments > PIPESGD_MAX_SEGMENTS) return PIPESGD_ERR_CAPACITY;
     const int mode = ring->mode, p = ring->workers;
+    Staging stg;
+    rc = check_workspace(ring, ws, PIPESGD_WS_PIPELINED, stg);
+    if (rc != PIPESGD_OK) return rc;
+    // time on the link for `tiles` tiles of one worker's payload (all workers' links run in parallel);
+    // the longest single delay is that of a whole ring block and must be one the stand-in accepts
+    const double tile_mib = static_cast<double>(pipesgd_payload_bytes(mode, kTile)) / (1024.0 * 1024.0);
+    auto link_us = [&](uint64_t tiles) { return static_cast<double>(link_us_per_mib) * tile_mib * static_cast<double>(tiles); };
+    if (link_us(slots) > 1.0e6) return PIPESGD_ERR_ARG;
     if (slots == 0) return PIPESGD_OK;
-    if (p > 1) {
-        if (!recv || (mode == PIPESGD_QUANT8 && !recv_scales)) return PIPESGD_ERR_ARG;
-        for (int r = 0; r < p; ++r) {
-            if (!recv[r] || (mode == PIPESGD_QUANT8 && !recv_scales[r])) return PIPESGD_ERR_ARG;
-            if (!aligned16(recv[r]) || (mode == PIPESGD_QUANT8 && !aligned16(recv_scales[r]))) return PIPESGD_ERR_ALIGN;
-        }
-    }
-    hipStream_t cs = static_cast<hipStream_t>(compute_stream), ws = static_cast<hipStream_t>(wire_stream);
+    void *const *recv = stg.stage;
+    float *const *recv_scales = stg.stage_sc;
+    hipStream_t cs = static_cast<hipStream_t>(compute_stream), ws_ = static_cast<hipStream_t>(wire_stream);
     const uint64_t S = static_cast<uint64_t>(segments) < slots ? static_cast<uint64_t>(segments) : slots;
     auto seg_lo = [&](uint64_t g) { return slots * g / S; };
-    // time on the link for `tiles` tiles of one worker's payload (all workers' links run in parallel)
-    const double tile_mib = static_cast<double>(pipesgd_payload_bytes(mode, kTile)) / (1024.0 * 1024.0);
     auto link_delay = [&](uint64_t tiles, hipStream_t st) -> int {
         if (link_us_per_mib <= 0.0f) return PIPESGD_OK;
-        return pipesgd_synthetic_compute(static_cast<float>(link_us_per_mib * tile_mib * static_cast<double>(tiles)), 1, st);
+        return pipesgd_synthetic_compute(static_cast<float>(link_us(tiles)), 1, st);
     };
 
-    // event layout: [0] entry, [1] done, then per segment: sent, and per (round, segment): copied, reduced
+    // events: entry, all reduced, done; per sub-block "sent"; per (round, sub-block) "copied" and "reduced".
+    // All of them exist before the first launch, so that running out of them cannot leave half an AllReduce enqueued.
+    const size_t events_needed = 3 + S + 2 * S * static_cast<size_t>(p > 1 ? p - 1 : 0);
+    try {
+        hipEvent_t unused;
+        if (!overlap_event(ov, events_needed - 1, &unused)) return PIPESGD_ERR_HIP;
+    } catch (const std::bad_alloc &) {
+        return PIPESGD_ERR_CAPACITY;
+    }
     size_t next_event = 0;
     auto record = [&](hipStream_t st, hipEvent_t *out_e) -> bool {
-        hipEvent_t e;
-        if (!overlap_event(ov, next_event++, &e)) return false;
+        hipEvent_t e = ov->events[next_event++];
         if (hipEventRecord(e, st) != hipSuccess) return false;
         *out_e = e;
         return true;
@@ -1066,10 +1125,11 @@ int pipesgd_allreduce_pipelined(const pipesgd_ring *ring, void *const *recv, flo
     auto wait = [&](hipStream_t st, hipEvent_t e) -> bool { return hipStreamWaitEvent(st, e, 0) == hipSuccess; };
 
     hipEvent_t entry;
-    if (!record(cs, &entry) || !wait(ws, entry)) return PIPESGD_ERR_HIP;
+    if (!record(cs, &entry) || !wait(ws_, entry)) return PIPESGD_ERR_HIP;
 
-    std::vector<hipEvent_t> ready(S, entry);          // per segment: what the next wire copy must wait for
-    for (uint64_t g = 0; g < S; ++g) {                // first send, segment by segment
+    hipEvent_t ready[PIPESGD_MAX_SEGMENTS];           // per sub-block: what the next wire copy must wait for
+    for (uint64_t g = 0; g < S; ++g) ready[g] = entry;
+    for (uint64_t g = 0; g < S; ++g) {                // first send, sub-block by sub-block
         RingArgs a = ra;
         a.slot_base = static_cast<uint32_t>(seg_lo(g));
         rc = first_send_impl(mode, a, bt, seg_lo(g + 1) - seg_lo(g), cs);
@@ -1079,7 +1139,7 @@ int pipesgd_allreduce_pipelined(const pipesgd_ring *ring, void *const *recv, flo
     for (int step = 0; step <= p - 2; ++step) {
         for (uint64_t g = 0; g < S; ++g) {
             const uint64_t count = seg_lo(g + 1) - seg_lo(g);
-            // stage 1, "compressed communication": the sender's payload travels into the receiver's staging
+            // stage 1, the compressed communication: the sender's payload travels into the receiver's staging
             RingArgs w = ra;
             w.slot_base = static_cast<uint32_t>(seg_lo(g));
             for (int r = 0; r < p; ++r) {
@@ -1087,20 +1147,20 @@ int pipesgd_allreduce_pipelined(const pipesgd_ring *ring, void *const *recv, flo
                 w.in[r] = (mode == PIPESGD_NONE && step == 0) ? static_cast<const void *>(ra.g[src]) : ra.out[src];
                 w.in_sc[r] = ra.out_sc[src];
                 w.out[r] = recv[r];
-                w.out_sc[r] = mode == PIPESGD_QUANT8 ? recv_scales[r] : nullptr;
+                w.out_sc[r] = recv_scales[r];
             }
-            if (!wait(ws, ready[g])) return PIPESGD_ERR_HIP;
-            rc = link_delay(count, ws);               // the payload is under way for this long, then it lands
-            if (rc == PIPESGD_OK) rc = copy_impl(mode, w, bt, count, step + 1, static_cast<uint32_t>(wire_workgroups), ws);
+            if (!wait(ws_, ready[g])) return PIPESGD_ERR_HIP;
+            rc = link_delay(count, ws_);              // the payload is under way for this long, then it lands
+            if (rc == PIPESGD_OK) rc = copy_impl(mode, w, bt, count, step + 1, static_cast<uint32_t>(wire_workgroups), ws_);
             if (rc != PIPESGD_OK) return rc;
             hipEvent_t copied;
-            if (!record(ws, &copied) || !wait(cs, copied)) return PIPESGD_ERR_HIP;
+            if (!record(ws_, &copied) || !wait(cs, copied)) return PIPESGD_ERR_HIP;
             // stage 2, (decompress, sum, compress) on what has arrived
             RingArgs h = ra;
             h.slot_base = static_cast<uint32_t>(seg_lo(g));
             for (int r = 0; r < p; ++r) {
                 h.in[r] = recv[r];
-                h.in_sc[r] = mode == PIPESGD_QUANT8 ? recv_scales[r] : nullptr;
+                h.in_sc[r] = recv_scales[r];
             }
             rc = rs_impl(mode, h, bt, count, step, true, cs);
             if (rc != PIPESGD_OK) return rc;
@@ -1109,14 +1169,14 @@ int pipesgd_allreduce_pipelined(const pipesgd_ring *ring, void *const *recv, flo
     }
     // send-back rounds: communication only, on the wire stream, after the last reductions
     hipEvent_t reduced_all;
-    if (!record(cs, &reduced_all) || !wait(ws, reduced_all)) return PIPESGD_ERR_HIP;
+    if (!record(cs, &reduced_all) || !wait(ws_, reduced_all)) return PIPESGD_ERR_HIP;
     for (int step = 0; step <= p - 2; ++step) {
-        rc = link_delay(slots, ws);
-        if (rc == PIPESGD_OK) rc = copy_impl(mode, ra, bt, slots, step, static_cast<uint32_t>(wire_workgroups), ws);
+        rc = link_delay(slots, ws_);
+        if (rc == PIPESGD_OK) rc = copy_impl(mode, ra, bt, slots, step, static_cast<uint32_t>(wire_workgroups), ws_);
         if (rc != PIPESGD_OK) return rc;
     }
     hipEvent_t done;
-    if (!record(ws, &done) || !wait(cs, done)) return PIPESGD_ERR_HIP;
+    if (!record(ws_, &done) || !wait(cs, done)) return PIPESGD_ERR_HIP;
     return PIPESGD_OK;
 }
 
@@ -1155,7 +1215,7 @@ int pipesgd_apply_update_multi(int mode, int replicas, const void *const *g_sum_
     if (rc != PIPESGD_OK) return rc;
     if (n == 0) return PIPESGD_OK;
     const bool mom = momentum != 0.0f;
-    const LaunchConfig c = g_cfg[kUpdate][mode];
+    const LaunchConfig c = cfg_of(kUpdate, mode);
     hipStream_t s = static_cast<hipStream_t>(stream);
 #define CALL(M) return mom ? launch_update<M, true>(c, ua, replicas, s) : launch_update<M, false>(c, ua, replicas, s);
     PIPESGD_MODE_SWITCH(mode, CALL)
@@ -1227,3 +1287,21 @@ int pipesgd_unpack(const pipesgd_segment *segments, uint64_t num, uint64_t total
 }
 
 }  // extern "C"
+
+int pipesgd_internal_check_allreduce(const pipesgd_ring *ring, int schedule)
+{
+    RingArgs ra; BucketTable bt; uint64_t slots = 0;
+    const int rc = prepare_ring(ring, ra, bt, slots);
+    if (rc != PIPESGD_OK) return rc;
+    return (schedule == PIPESGD_STEPWISE || schedule == PIPESGD_FUSED) ? PIPESGD_OK : PIPESGD_ERR_MODE;
+}
+
+int pipesgd_internal_check_update(int mode, int replicas, const void *const *g_sum_c, const float *const *scales,
+                                  uint64_t n, float *const *w, float *const *v, float momentum)
+{
+    UpdateArgs ua;
+    int rc = prepare_update(mode, replicas, g_sum_c, scales, n, w, v, 0.0f, momentum, 1.0f, ua);
+    if (rc == PIPESGD_OK && (n + 1023) / 1024 > 0x7fffffffull) rc = PIPESGD_ERR_CAPACITY;   // more units than a grid holds
+    return rc;
+}
+

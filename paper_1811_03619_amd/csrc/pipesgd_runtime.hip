@@ -1,13 +1,15 @@
 // The per-worker runtime of Algorithm 1 (arXiv 1811.03619) on one GPU: the
 // paper's compute thread and communication thread become two HIP streams, its
 // "ready" flags become HIP events.  Built on the library's public entry points
-// only; the one kernel here is the stand-in for forward + backward.
+// (and their launch-free argument checks); the one kernel here is the stand-in
+// for forward + backward.
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
 #include <new>
 
 #include "pipesgd.h"
+#include "pipesgd_internal.hpp"
 
 namespace {
 
@@ -89,7 +91,8 @@ int pipesgd_runtime_sync(pipesgd_runtime *rt)
 
 int pipesgd_synthetic_compute(float duration_us, int workgroups, void *stream)
 {
-    if (!(duration_us >= 0.0f) || duration_us > 1.0e6f || workgroups < 1 || workgroups > 65535) return PIPESGD_ERR_ARG;
+    const int rc = pipesgd_internal_check_standin(duration_us, workgroups);
+    if (rc != PIPESGD_OK) return rc;
     if (duration_us == 0.0f) return PIPESGD_OK;
     const uint64_t ticks = static_cast<uint64_t>(static_cast<double>(duration_us) * 100.0);   // 100 MHz
     hipLaunchKernelGGL(synthetic_compute_kernel, dim3(workgroups), dim3(64), 0, static_cast<hipStream_t>(stream),
@@ -101,10 +104,22 @@ int pipesgd_runtime_iteration(pipesgd_runtime *rt, const pipesgd_runtime_iter *i
 {
     if (!rt || !rt->ok || !it || !it->ring) return PIPESGD_ERR_ARG;
     if (it->width < 1 || it->width >= kEventRing || it->reserved != 0) return PIPESGD_ERR_ARG;
+    const int wg = it->compute_workgroups > 0 ? it->compute_workgroups : 1;
+    // Everything is checked here, before the first launch or event record: a rejected call leaves both
+    // streams, the events and the iteration count as they were, and the same iteration can be issued again.
+    int rc = pipesgd_internal_check_allreduce(it->ring, it->schedule);
+    if (rc == PIPESGD_OK) {
+        const bool sync = it->width == 1;
+        rc = pipesgd_internal_check_update(it->ring->mode, it->replicas, sync ? it->fresh_g_sum_c : it->stale_g_sum_c,
+                                           sync ? it->fresh_scales : it->stale_scales, it->ring->n, it->w, it->v,
+                                           it->momentum);
+    }
+    if (rc == PIPESGD_OK) rc = pipesgd_internal_check_standin(it->compute_us, wg);
+    if (rc == PIPESGD_OK) rc = pipesgd_internal_check_standin(it->wire_us, 1);
+    if (rc != PIPESGD_OK) return rc;
+
     const uint64_t t = rt->t + 1;                       // this call is iteration t (1-based)
     hipEvent_t sum_ready = rt->sum_ready[t % kEventRing];
-    int rc;
-    const int wg = it->compute_workgroups > 0 ? it->compute_workgroups : 1;
 
     if (it->width >= 2) {
         // Indexing: g[t] is the gradient evaluated at w[t-1]; A[t] = AllReduce(g[t]);
@@ -150,3 +165,9 @@ int pipesgd_runtime_iteration(pipesgd_runtime *rt, const pipesgd_runtime_iter *i
 }
 
 }  // extern "C"
+
+int pipesgd_internal_check_standin(float duration_us, int workgroups)
+{
+    if (!(duration_us >= 0.0f) || duration_us > 1.0e6f || workgroups < 1 || workgroups > 65535) return PIPESGD_ERR_ARG;
+    return PIPESGD_OK;
+}

@@ -85,6 +85,9 @@ class PipeSgdSim:
             assert ws[0] == self.stage[0].numel() * self.stage[0].element_size()
             assert ws[1] == (self.stage_scales[0].numel() * 4 if mode == B.QUANT8 else 0)
             assert ws[2] == (self.partial[0].numel() * 4 if self.partial is not None else 0)
+        self.workspace = None
+        if self.stage is not None:
+            self.workspace = B.make_workspace(self.stage, self.stage_scales if mode == B.QUANT8 else None, self.partial)
         self.t = 0
 
     # -- data in / out (host <-> device copies; plumbing) --
@@ -115,10 +118,9 @@ class PipeSgdSim:
         """Enqueue the AllReduce of the current gradients; returns the slot index."""
         i = (self.t + 1) % len(self.rings)
         if self.schedule == B.DIRECT:
-            B.allreduce_direct(self.rings[i], self.stage, self.stage_scales if self.mode == B.QUANT8 else None, stream)
+            B.allreduce_direct(self.rings[i], self.workspace, stream)
         elif self.schedule == B.HALVING_DOUBLING:
-            B.allreduce_halving_doubling(self.rings[i], self.stage,
-                                         self.stage_scales if self.mode == B.QUANT8 else None, self.partial, stream)
+            B.allreduce_halving_doubling(self.rings[i], self.workspace, stream)
         else:
             B.allreduce_sim(self.rings[i], B.FUSED if self.schedule == B.ONE_LAUNCH else self.schedule, stream)
         self._last = i

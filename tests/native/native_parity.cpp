@@ -107,6 +107,9 @@ static int run_case(int mode, int p, size_t n)
     }
     std::vector<float *> stage_sc(p), partial(p);
     for (int r = 0; r < p; ++r) { stage_sc[r] = static_cast<float *>(dstage_sc.ptr[r]); partial[r] = static_cast<float *>(dpartial.ptr[r]); }
+    pipesgd_workspace ws;
+    ws.stage = dstage.ptr.data(); ws.stage_scales = stage_sc.data(); ws.partial = partial.data();
+    ws.stage_bytes = pb; ws.stage_scales_bytes = 4 * ns; ws.partial_bytes = 4 * n;
 
     std::vector<std::vector<unsigned char>> want(p, std::vector<unsigned char>(pb + 1)), got(p, std::vector<unsigned char>(pb + 1));
     std::vector<std::vector<float>> want_sc(p, std::vector<float>(ns + 1)), got_sc(p, std::vector<float>(ns + 1));
@@ -127,8 +130,8 @@ static int run_case(int mode, int p, size_t n)
         switch (sched) {
         case 0: LIB_OK(pipesgd_allreduce_sim(&ring, PIPESGD_STEPWISE, nullptr)); break;
         case 1: LIB_OK(pipesgd_allreduce_sim(&ring, PIPESGD_FUSED, nullptr)); break;
-        case 2: LIB_OK(pipesgd_allreduce_direct(&ring, dstage.ptr.data(), stage_sc.data(), nullptr)); break;
-        default: LIB_OK(pipesgd_allreduce_halving_doubling(&ring, dstage.ptr.data(), stage_sc.data(), partial.data(), nullptr)); break;
+        case 2: LIB_OK(pipesgd_allreduce_direct(&ring, &ws, nullptr)); break;
+        default: LIB_OK(pipesgd_allreduce_halving_doubling(&ring, &ws, nullptr)); break;
         }
         HIP_OK(hipDeviceSynchronize());
         if (sched <= 1) orc_allreduce(mode, p, n, gp.data(), wp.data(), wsp.data());

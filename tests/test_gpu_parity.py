@@ -525,7 +525,7 @@ def test_allreduce_pipelined_equals_oracle(orc, mode, p, n, segments, two_stream
         if rep == 1:
             for t in slots:
                 t.fill_(0x33 if mode != B.NONE else 7.0)
-        B.allreduce_pipelined(ring, recv, recv_sc if mode == B.QUANT8 else None, segments, ov,
+        B.allreduce_pipelined(ring, B.make_workspace(recv, recv_sc if mode == B.QUANT8 else None), segments, ov,
                               None, wire if two_streams else None, wire_workgroups=(0 if rep == 0 else 3),
                               link_us_per_mib=(0.0 if rep == 0 else 20.0))
         sync()
@@ -557,7 +557,7 @@ def test_allreduce_pipelined_with_buckets(orc, mode, segments):
     recv_sc = [dev_zeros(B.num_scales(mode, N), fill=-2.0) for _ in range(p)]
     ring = B.make_ring(mode, N, g_dev, slots, scs if mode == B.QUANT8 else None, buckets)
     ov, rt = B.Overlap(), B.Runtime()
-    B.allreduce_pipelined(ring, recv, recv_sc if mode == B.QUANT8 else None, segments, ov, rt.stream(0), rt.stream(1),
+    B.allreduce_pipelined(ring, B.make_workspace(recv, recv_sc if mode == B.QUANT8 else None), segments, ov, rt.stream(0), rt.stream(1),
                           link_us_per_mib=10.0)
     rt.sync()
     sync()
@@ -578,9 +578,9 @@ def test_allreduce_pipelined_rejects_bad_arguments():
     ov = B.Overlap()
     ring = B.make_ring(B.TRUNC16, n, g, slots, None)
     with pytest.raises(B.PipeSgdError):
-        B.allreduce_pipelined(ring, recv, None, 0, ov)
+        B.allreduce_pipelined(ring, B.make_workspace(recv), 0, ov)
     with pytest.raises(B.PipeSgdError):
-        B.allreduce_pipelined(ring, [recv[0], None], None, 2, ov)
+        B.allreduce_pipelined(ring, B.make_workspace([recv[0], None]), 2, ov)
     sync()
 
 
@@ -647,6 +647,74 @@ def test_runtime_rejects_widths_it_has_no_events_for():
         with pytest.raises(B.PipeSgdError):
             rt.iteration(sim.rings[0], sim.updates[1], sim.updates[0], B.STEPWISE, width, 0.01, 0.0)
     rt.sync()
+    rt.close()
+
+
+@pytest.mark.parametrize("width", [1, 2])
+def test_runtime_rejected_call_enqueues_nothing_and_the_runtime_goes_on(orc, width):
+    # Every field of the iteration is checked before the first launch or event record: a call with one bad
+    # field returns its error with nothing in flight (the slots the AllReduce would write keep their poison),
+    # the iteration count is not advanced, and the same iteration issued correctly afterwards gives the oracle's bits.
+    import ctypes as C
+    mode, p, n, lr, m, iters = B.TRUNC16, 4, 4096 * 6 + 33, 0.01, 0.9, 5
+    grad_fn = lambda r, w, t: W.gaussian(n, 1e-3, 31, (width, r, t, 0))
+    w0 = W.gaussian(n, 0.05, 33)
+    sim = PipeSgdSim(mode, p, n, lr, m, 1.0, 2)
+    sim.set_model(w0)
+    sync()
+    rt = B.Runtime()
+    L = B.lib()
+
+    def make_iter(ring, stale, fresh):
+        it = B.RuntimeIter()
+        it.ring = C.pointer(ring)
+        it.schedule, it.width, it.replicas, it.compute_workgroups = B.STEPWISE, width, p, 2
+        it.compute_us, it.wire_us, it.lr, it.momentum, it.grad_scale, it.reserved = 20.0, 10.0, lr, m, 1.0, 0
+        it.stale_g_sum_c = C.cast(stale.g_sum_c, C.c_void_p)
+        it.fresh_g_sum_c = C.cast(fresh.g_sum_c, C.c_void_p)
+        it.w, it.v = C.cast(stale.w, C.c_void_p), C.cast(stale.v, C.c_void_p)
+        return it
+
+    used = "fresh_g_sum_c" if width == 1 else "stale_g_sum_c"
+    bad_w = (C.c_void_p * p)(*[sim.w[r].data_ptr() + (4 if r == 2 else 0) for r in range(p)])
+    mutations = [
+        (lambda it: setattr(it, "w", None), -1),
+        (lambda it: setattr(it, "v", None), -1),                       # momentum without v
+        (lambda it: setattr(it, used, None), -1),
+        (lambda it: setattr(it, "w", C.cast(bad_w, C.c_void_p)), -2),
+        (lambda it: setattr(it, "replicas", 0), -1),
+        (lambda it: setattr(it, "replicas", 17), -4),
+        (lambda it: setattr(it, "compute_us", -1.0), -1),
+        (lambda it: setattr(it, "compute_us", 2.0e6), -1),
+        (lambda it: setattr(it, "wire_us", float("nan")), -1),
+        (lambda it: setattr(it, "compute_workgroups", 70000), -1),
+        (lambda it: setattr(it, "schedule", 7), -3),
+        (lambda it: setattr(it, "reserved", 1), -1),
+    ]
+    for t in range(1, iters + 1):
+        rt.sync()
+        sim.set_gradients([grad_fn(r, None, t) for r in range(p)])
+        cur = t % 2
+        if t == 3:
+            for r in range(p):
+                sim.slots[cur][r].fill_(0x5A5A)
+            sync()
+            for mutate, want_rc in mutations:
+                it = make_iter(sim.rings[cur], sim.updates[1 - cur], sim.updates[cur])
+                mutate(it)
+                assert L.pipesgd_runtime_iteration(rt.handle, C.byref(it)) == want_rc, want_rc
+            rt.sync()
+            sync()
+            for r in range(p):                                         # the AllReduce was never enqueued
+                assert bool((sim.slots[cur][r] == 0x5A5A).all()), r
+        sync()
+        it = make_iter(sim.rings[cur], sim.updates[1 - cur], sim.updates[cur])
+        assert L.pipesgd_runtime_iteration(rt.handle, C.byref(it)) == 0
+    rt.sync()
+    ws, vs = orc.pipe_sgd_run(mode, grad_fn, w0, p, iters, lr, m, 1.0, width)
+    for r in range(p):
+        assert_fp32_close_then_exact(sim.model(r), ws[r], f"w r={r}")
+        assert_fp32_close_then_exact(sim.velocity(r), vs[r], f"v r={r}")
     rt.close()
 
 
@@ -752,7 +820,7 @@ def test_allreduce_direct_equals_oracle(orc, mode, p, n):
     stage = [pay_buf(mode, n) for _ in range(p)]
     stage_sc = [dev_zeros(B.num_scales(mode, n), fill=-2.0) for _ in range(p)]
     ring = B.make_ring(mode, n, g_dev, slots, scs if mode == B.QUANT8 else None)
-    B.allreduce_direct(ring, stage, stage_sc if mode == B.QUANT8 else None)
+    B.allreduce_direct(ring, B.make_workspace(stage, stage_sc if mode == B.QUANT8 else None))
     sync()
     for r in range(p):
         if mode == B.NONE:
@@ -787,7 +855,7 @@ def test_allreduce_direct_bucketed_and_hand_cases(orc, mode):
     stage = [pay_buf(mode, N) for _ in range(p)]
     stage_sc = [dev_zeros(B.num_scales(mode, N)) for _ in range(p)]
     ring = B.make_ring(mode, N, g_dev, slots, scs if mode == B.QUANT8 else None, buckets)
-    B.allreduce_direct(ring, stage, stage_sc if mode == B.QUANT8 else None)
+    B.allreduce_direct(ring, B.make_workspace(stage, stage_sc if mode == B.QUANT8 else None))
     sync()
     for r in range(p):
         assert_bits_equal(down(slots[r], mode), pays[r], f"payload r={r}")
@@ -807,7 +875,7 @@ def test_allreduce_direct_bucketed_and_hand_cases(orc, mode):
     stage = [pay_buf(mode, 2 * ce) for _ in range(2)]
     stage_sc = [dev_zeros(2) for _ in range(2)]
     ring = B.make_ring(mode, 2 * ce, g_dev, slots, scs if mode == B.QUANT8 else None)
-    B.allreduce_direct(ring, stage, stage_sc if mode == B.QUANT8 else None)
+    B.allreduce_direct(ring, B.make_workspace(stage, stage_sc if mode == B.QUANT8 else None))
     sync()
     got = down(slots[1], mode)
     if mode == B.TRUNC16:
@@ -835,7 +903,7 @@ def test_allreduce_halving_doubling_equals_oracle(orc, mode, p, n):
     stage, stage_sc, partial = hd_buffers(mode, n, p)
     ring = B.make_ring(mode, n, g_dev, slots, scs if mode == B.QUANT8 else None)
     for _ in range(2):                 # a second call on used scratch buffers gives the same result
-        B.allreduce_halving_doubling(ring, stage, stage_sc, partial)
+        B.allreduce_halving_doubling(ring, B.make_workspace(stage, stage_sc, partial))
         sync()
         for r in range(p):
             if mode == B.NONE:
@@ -868,7 +936,7 @@ def test_allreduce_halving_doubling_bucketed_and_hand_cases(orc, mode):
     scs = [dev_zeros(B.num_scales(mode, N)) for _ in range(p)]
     stage, stage_sc, partial = hd_buffers(mode, N, p, poison=False)
     ring = B.make_ring(mode, N, g_dev, slots, scs if mode == B.QUANT8 else None, buckets)
-    B.allreduce_halving_doubling(ring, stage, stage_sc, partial)
+    B.allreduce_halving_doubling(ring, B.make_workspace(stage, stage_sc, partial))
     sync()
     for r in range(p):
         assert_bits_equal(down(slots[r], mode), pays[r], f"payload r={r}")
@@ -892,7 +960,7 @@ def test_allreduce_halving_doubling_bucketed_and_hand_cases(orc, mode):
     g_dev, slots, scs = ring_buffers(mode, g)
     stage, stage_sc, partial = hd_buffers(mode, p * ce, p)
     ring = B.make_ring(mode, p * ce, g_dev, slots, scs if mode == B.QUANT8 else None)
-    B.allreduce_halving_doubling(ring, stage, stage_sc, partial)
+    B.allreduce_halving_doubling(ring, B.make_workspace(stage, stage_sc, partial))
     sync()
     for r in range(p):
         got = down(slots[r], mode)
@@ -910,15 +978,15 @@ def test_allreduce_halving_doubling_rejects_bad_arguments():
         stage, stage_sc, partial = hd_buffers(B.TRUNC16, n, p)
         partial = partial or [dev_zeros(n) for _ in range(p)]
         with pytest.raises(B.PipeSgdError):
-            B.allreduce_halving_doubling(sim.rings[0], stage, None, partial)
+            B.allreduce_halving_doubling(sim.rings[0], B.make_workspace(stage, None, partial))
     sim = PipeSgdSim(B.QUANT8, 4, n, 0.01, 0.9)
     stage, stage_sc, partial = hd_buffers(B.QUANT8, n, 4)
     with pytest.raises(B.PipeSgdError):
-        B.allreduce_halving_doubling(sim.rings[0], stage, None, partial)          # scales of the send buffers missing
+        B.allreduce_halving_doubling(sim.rings[0], B.make_workspace(stage, None, partial))          # scales of the send buffers missing
     with pytest.raises(B.PipeSgdError):
-        B.allreduce_halving_doubling(sim.rings[0], stage, stage_sc, None)         # partial sums missing at p > 2
+        B.allreduce_halving_doubling(sim.rings[0], B.make_workspace(stage, stage_sc, None))         # partial sums missing at p > 2
     with pytest.raises(B.PipeSgdError):
-        B.allreduce_halving_doubling(sim.rings[0], None, stage_sc, partial)
+        B.allreduce_halving_doubling(sim.rings[0], B.make_workspace(None, stage_sc, partial))
     sync()
 
 
@@ -990,7 +1058,7 @@ def test_random_shapes_all_schedules(orc, case):
         g_dev2, slots2, scs2 = ring_buffers(mode, grads, poison=not buckets)
         stage, stage_sc, partial = hd_buffers(mode, n, p, poison=not buckets)
         ring2 = B.make_ring(mode, n, g_dev2, slots2, scs2 if mode == B.QUANT8 else None, buckets)
-        B.allreduce_halving_doubling(ring2, stage, stage_sc, partial)
+        B.allreduce_halving_doubling(ring2, B.make_workspace(stage, stage_sc, partial))
         sync()
         for r in range(p):
             assert_bits_equal(down(slots2[r], mode), want_hd[r][0], f"payload r={r} halving-doubling")

@@ -131,28 +131,92 @@ def test_ring_validation_errors():
     assert L.pipesgd_ring_first_send(C.byref(fake_ring(n=0, g=0, pay=0, sc=0)), None) == 0
 
 
+def fake_workspace(p=4, mode=B.NONE, n=8192, schedule=None, stage=0x40000, stage_sc=0x48000, partial=0x50000,
+                   shrink=(0, 0, 0)):
+    """A workspace of never-dereferenced addresses, sized as the library asks
+    for `schedule` minus `shrink` bytes per table."""
+    need = B.workspace_bytes(schedule, mode, n, p)
+    arr = lambda v: None if v is None else [v] * p
+    return B.make_workspace(arr(stage), arr(stage_sc), arr(partial),
+                            sizes=tuple(max(0, a - b) for a, b in zip(need, shrink)))
+
+
 def test_extra_schedules_validate_before_launching():
     # every call below is rejected (or is a no-op) on the host: nothing is enqueued
     L = B.lib()
-    arr = lambda vals: (C.c_void_p * len(vals))(*vals)
-    hd = L.pipesgd_allreduce_halving_doubling
-    good = arr([0x40000] * 4)
-    assert hd(None, good, good, good, None) == -1
+    hd = lambda ring, ws: L.pipesgd_allreduce_halving_doubling(C.byref(ring) if ring is not None else None,
+                                                               C.byref(ws) if ws is not None else None, None)
+    HD, DI, PI = B.WS_HALVING_DOUBLING, B.WS_DIRECT, B.WS_PIPELINED
+    assert hd(None, fake_workspace(schedule=HD)) == -1
     for p in (3, 5, 6, 12):                                 # worker count must be a power of two
-        assert hd(C.byref(fake_ring(p=p)), arr([0x40000] * p), None, arr([0x50000] * p), None) == -1
-    assert hd(C.byref(fake_ring()), None, None, good, None) == -1                     # no send buffers
-    assert hd(C.byref(fake_ring()), good, None, None, None) == -1                     # p > 2 needs partial sums
-    assert hd(C.byref(fake_ring()), arr([0x40000, 0, 0x40000, 0x40000]), None, good, None) == -1
-    assert hd(C.byref(fake_ring()), arr([0x40004] * 4), None, good, None) == -2
-    assert hd(C.byref(fake_ring()), good, None, arr([0x50008] * 4), None) == -2
-    assert hd(C.byref(fake_ring(mode=B.QUANT8)), good, None, good, None) == -1        # send-buffer scales missing
-    assert hd(C.byref(fake_ring(mode=9)), good, good, good, None) == -3
-    assert hd(C.byref(fake_ring(n=0, g=0, pay=0, sc=0)), None, None, None, None) == 0  # empty vector: nothing to do
-    direct = L.pipesgd_allreduce_direct
-    assert direct(C.byref(fake_ring()), None, None, None) == -1
-    assert direct(C.byref(fake_ring()), arr([0x40004] * 4), None, None) == -2
-    assert direct(C.byref(fake_ring(mode=B.QUANT8)), good, None, None) == -1
-    assert direct(C.byref(fake_ring(n=0, g=0, pay=0, sc=0)), None, None, None) == 0
+        assert hd(fake_ring(p=p), fake_workspace(p=p, schedule=HD)) == -1
+    assert hd(fake_ring(), None) == -1                                                  # no workspace at all
+    assert hd(fake_ring(), fake_workspace(schedule=HD, stage=None)) == -1               # no send buffers
+    assert hd(fake_ring(), fake_workspace(schedule=HD, partial=None)) == -1             # p > 2 needs partial sums
+    ws = fake_workspace(schedule=HD)
+    ws._keepalive[0][1] = None
+    assert hd(fake_ring(), ws) == -1                                                    # one send buffer missing
+    assert hd(fake_ring(), fake_workspace(schedule=HD, stage=0x40004)) == -2
+    assert hd(fake_ring(), fake_workspace(schedule=HD, partial=0x50008)) == -2
+    assert hd(fake_ring(mode=B.QUANT8), fake_workspace(mode=B.QUANT8, schedule=HD, stage_sc=None)) == -1
+    assert hd(fake_ring(mode=9), fake_workspace(schedule=HD)) == -3
+    assert hd(fake_ring(n=0, g=0, pay=0, sc=0), None) == 0                              # empty vector: nothing to do
+    direct = lambda ring, ws: L.pipesgd_allreduce_direct(C.byref(ring), C.byref(ws) if ws is not None else None, None)
+    assert direct(fake_ring(), None) == -1
+    assert direct(fake_ring(), fake_workspace(schedule=DI, stage=0x40004)) == -2
+    assert direct(fake_ring(mode=B.QUANT8), fake_workspace(mode=B.QUANT8, schedule=DI, stage_sc=None)) == -1
+    assert direct(fake_ring(n=0, g=0, pay=0, sc=0), None) == 0
+
+
+@pytest.mark.parametrize("mode", [B.NONE, B.TRUNC16, B.QUANT8])
+def test_undersized_workspace_is_refused_on_the_host(mode):
+    # an under-allocated staging buffer would be overrun by the kernels: the sizes the caller states are
+    # compared with pipesgd_workspace_bytes before anything is launched
+    L = B.lib()
+    n, p = 4096 * 5 + 7, 4
+    ring = fake_ring(p=p, mode=mode, n=n)
+    calls = {
+        B.WS_DIRECT: lambda ws: L.pipesgd_allreduce_direct(C.byref(ring), C.byref(ws), None),
+        B.WS_HALVING_DOUBLING: lambda ws: L.pipesgd_allreduce_halving_doubling(C.byref(ring), C.byref(ws), None),
+        B.WS_PIPELINED: lambda ws: L.pipesgd_allreduce_pipelined(C.byref(ring), C.byref(ws), 2, 0, 0.0, 0x1234, None, None),
+    }
+    for sched, call in calls.items():
+        need = B.workspace_bytes(sched, mode, n, p)
+        assert call(fake_workspace(p, mode, n, sched, shrink=(1, 0, 0))) == -4, sched
+        if need[1]:
+            assert call(fake_workspace(p, mode, n, sched, shrink=(0, 1, 0))) == -4, sched
+        if need[2]:
+            assert call(fake_workspace(p, mode, n, sched, shrink=(0, 0, 4))) == -4, sched
+    assert "workspace" in B.strerror(-4)
+
+
+def test_scales_are_only_looked_at_when_quantising():
+    # ring->scales[] is documented as QUANT8-only: garbage there must not fail the other modes
+    L = B.lib()
+    for mode in (B.NONE, B.TRUNC16):
+        ring = fake_ring(mode=mode, sc=0x30004)             # misaligned, and never read
+        assert L.pipesgd_ring_reduce_scatter_step(C.byref(ring), 5, None) == -1    # reaches the step check
+        ring = fake_ring(mode=mode, sc=0)
+        assert L.pipesgd_ring_reduce_scatter_step(C.byref(ring), 5, None) == -1
+    assert L.pipesgd_ring_reduce_scatter_step(C.byref(fake_ring(mode=B.QUANT8, sc=0x30004)), 0, None) == -2
+
+
+def test_pipelined_schedule_validates_before_launching():
+    L = B.lib()
+    n, p = 4096 * 64, 4
+    ring = fake_ring(p=p, mode=B.TRUNC16, n=n)
+    ws = fake_workspace(p, B.TRUNC16, n, B.WS_PIPELINED)
+    call = lambda segments, wg=0, link=0.0, ov=0x1234, w=ws: L.pipesgd_allreduce_pipelined(
+        C.byref(ring), C.byref(w) if w is not None else None, segments, wg, C.c_float(link), ov, None, None)
+    assert call(0) == -1 and call(-3) == -1
+    assert call(65) == -4                                   # more sub-blocks than the library keeps events for
+    assert call(2, wg=-1) == -1
+    assert call(2, link=-1.0) == -1 and call(2, link=float("nan")) == -1
+    assert call(2, ov=None) == -1
+    assert call(2, w=None) == -1
+    # a link so slow that one ring block would be under way for more than a second: refused up front
+    # (16 tiles of 8 KiB per ring block = 0.125 MiB; 1e7 us per MiB -> 1.25 s)
+    assert call(2, link=1.0e7) == -1
 
 
 @pytest.mark.parametrize("mode", [B.NONE, B.TRUNC16, B.QUANT8])
