@@ -210,6 +210,25 @@ typedef struct pipesgd_workspace {
  * be NULL for one worker or an empty vector.  Buckets are supported. */
 int pipesgd_allreduce_direct(const pipesgd_ring *ring, const pipesgd_workspace *ws, void *stream);
 
+/* pipesgd_allreduce_direct for callers that cannot allocate device memory and
+ * have none to spare for the send buffers: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  The send buffers live in a
+ * device array of PIPESGD_STATIC_SCRATCH_BYTES bytes that is part of the
+ * library's code object (each GPU the library runs on holds its own copy until
+ * the process ends); the call allocates and frees nothing.  Same kernels and
+ * same result bits as pipesgd_allreduce_direct.
+ * The vector must fit:  p * (roundup256(pipesgd_payload_bytes(mode, n)) +
+ * roundup256(4 * pipesgd_num_scales(mode, n))) <= PIPESGD_STATIC_SCRATCH_BYTES,
+ * otherwise PIPESGD_ERR_CAPACITY (checked on the host before anything else).
+ * Every call on one GPU uses that GPU's one array: calls that may overlap on a
+ * GPU (different streams, different threads) race and must be ordered by the
+ * caller.  Nothing in the array has to be zero on entry -- every cell that is
+ * read was written earlier in the same call -- so it is never cleared and keeps
+ * the previous call's contents.  The first call on a device looks the array's
+ * address up (a query, no allocation); make that call outside graph capture. */
+#define PIPESGD_STATIC_SCRATCH_BYTES  (32u << 20)
+int pipesgd_allreduce_direct_static(const pipesgd_ring *ring, void *stream);
+
 /* A third AllReduce schedule: recursive halving and doubling, one of the
  * algorithms Sec. 3.1's closing remark names beside the ring (reduce-scatter by
  * recursive halving, all-gather by recursive doubling, as published by Thakur,

@@ -35,7 +35,9 @@ EXPORTS = [
     "pipesgd_model_sync_time", "pipesgd_model_pipe_ideal_time", "pipesgd_model_pipe_time",
     "pipesgd_model_ring_comm_time", "pipesgd_model_scaling_efficiency", "pipesgd_iteration_fused", "pipesgd_allreduce_direct",
     "pipesgd_allreduce_halving_doubling", "pipesgd_workspace_bytes", "pipesgd_placement_offset",
+    "pipesgd_allreduce_direct_static",
 ]
+STATIC_SCRATCH_BYTES = 32 << 20
 K_FIRST_SEND, K_REDUCE_SCATTER, K_ALLGATHER, K_FUSED, K_UPDATE, K_COMPRESS, K_DECOMPRESS = range(7)
 
 
@@ -163,6 +165,8 @@ def lib():
     L.pipesgd_model_ring_comm_time.argtypes = [i32, dbl, dbl, dbl, dbl, dbl, i32]
     L.pipesgd_allreduce_direct.restype = i32
     L.pipesgd_allreduce_direct.argtypes = [C.POINTER(RingStruct), C.POINTER(Workspace), vp]
+    L.pipesgd_allreduce_direct_static.restype = i32
+    L.pipesgd_allreduce_direct_static.argtypes = [C.POINTER(RingStruct), vp]
     L.pipesgd_placement_offset.restype = u64
     L.pipesgd_placement_offset.argtypes = [i32, i32, i32]
     L.pipesgd_workspace_bytes.restype = i32
@@ -335,6 +339,10 @@ def _ws_arg(ws: Optional[Workspace]):
 
 def allreduce_direct(ring: RingStruct, ws: Optional[Workspace], stream=None) -> None:
     check(lib().pipesgd_allreduce_direct(C.byref(ring), _ws_arg(ws), _stream(stream)), "pipesgd_allreduce_direct")
+
+
+def allreduce_direct_static(ring: RingStruct, stream=None) -> None:
+    check(lib().pipesgd_allreduce_direct_static(C.byref(ring), _stream(stream)), "pipesgd_allreduce_direct_static")
 
 
 def allreduce_halving_doubling(ring: RingStruct, ws: Optional[Workspace], stream=None) -> None:

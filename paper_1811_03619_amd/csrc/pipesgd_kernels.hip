@@ -822,6 +822,39 @@ int fused_impl(int mode, const RingArgs &ra, const BucketTable &bt, uint64_t slo
 
 }  // namespace
 
+// -------------------------------------------------- static scratch array --
+// Send buffers of pipesgd_allreduce_direct_static: part of the code object, so
+// every GPU that loads the library holds its own copy at its own address.  In
+// host code the name `scratch` is only a handle for hipGetSymbolAddress; the
+// device address it yields (kept per device below) is what the kernels get.
+static __device__ __align__(256) unsigned char scratch[PIPESGD_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::atomic<unsigned char *> g_scratch_ptr[kMaxDevices];
+
+// Device address of the current device's copy of `scratch`; looked up once per device.
+int scratch_base(unsigned char **out)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return PIPESGD_ERR_HIP;
+    if (dev < 0 || dev >= kMaxDevices) return PIPESGD_ERR_CAPACITY;
+    unsigned char *ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        void *sym = nullptr;
+        if (hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch)) != hipSuccess || !sym) return PIPESGD_ERR_HIP;
+        ptr = static_cast<unsigned char *>(sym);
+        g_scratch_ptr[dev].store(ptr, std::memory_order_release);
+    }
+    *out = ptr;
+    return PIPESGD_OK;
+}
+
+inline uint64_t round_up_256(uint64_t x) { return (x + 255) / 256 * 256; }
+
+}  // namespace
+
 // ------------------------------------------------------------ entry points --
 
 extern "C" {
@@ -963,6 +996,35 @@ int pipesgd_allreduce_direct(const pipesgd_ring *ring, const pipesgd_workspace *
     if (rc != PIPESGD_OK) return rc;
     if (slots == 0) return PIPESGD_OK;
     return direct_impl(ring->mode, ra, bt, slots, st, static_cast<hipStream_t>(stream));
+}
+
+int pipesgd_allreduce_direct_static(const pipesgd_ring *ring, void *stream)
+{
+    RingArgs ra; BucketTable bt; uint64_t slots = 0;
+    int rc = prepare_ring(ring, ra, bt, slots);
+    if (rc != PIPESGD_OK) return rc;
+    const int mode = ring->mode, p = ring->workers;
+    // the p send buffers and their scales, each at a multiple of 256 bytes of the array
+    const uint64_t pay_stride = round_up_256(pipesgd_payload_bytes(mode, ring->n));
+    const uint64_t sc_stride = round_up_256(4 * pipesgd_num_scales(mode, ring->n));
+    if (pay_stride > PIPESGD_STATIC_SCRATCH_BYTES || sc_stride > PIPESGD_STATIC_SCRATCH_BYTES ||
+        static_cast<uint64_t>(p) * (pay_stride + sc_stride) > PIPESGD_STATIC_SCRATCH_BYTES)
+        return PIPESGD_ERR_CAPACITY;
+    if (slots == 0) return PIPESGD_OK;
+    Staging st;
+    for (int r = 0; r < kMaxW; ++r) { st.stage[r] = nullptr; st.stage_sc[r] = nullptr; st.partial[r] = nullptr; }
+    if (p > 1) {
+        unsigned char *base = nullptr;
+        rc = scratch_base(&base);
+        if (rc != PIPESGD_OK) return rc;
+        for (int r = 0; r < p; ++r) {
+            st.stage[r] = base + static_cast<uint64_t>(r) * pay_stride;
+            if (mode == PIPESGD_QUANT8)
+                st.stage_sc[r] = reinterpret_cast<float *>(base + static_cast<uint64_t>(p) * pay_stride +
+                                                           static_cast<uint64_t>(r) * sc_stride);
+        }
+    }
+    return direct_impl(mode, ra, bt, slots, st, static_cast<hipStream_t>(stream));
 }
 
 // ------------------------------------------ recursive halving and doubling --

@@ -292,6 +292,21 @@ def test_codec_and_update_validation_errors():
     assert L.pipesgd_pack(None, 0, 0, None) == 0
 
 
+def test_static_scratch_capacity_is_checked_on_the_host():
+    # needs no device memory: the addresses are never dereferenced
+    L = B.lib()
+    cap = B.STATIC_SCRATCH_BYTES
+    ring_of = lambda mode, n, p: B.make_ring(mode, n, [0x10000] * p, [0x20000] * p, [0x30000] * p)
+    call = lambda ring: L.pipesgd_allreduce_direct_static(C.byref(ring), None)
+    assert call(ring_of(B.NONE, cap // 4 // 4 + 4096, 4)) == -4
+    assert call(ring_of(B.TRUNC16, cap // 2 // 4 + 4096, 4)) == -4
+    assert call(ring_of(B.QUANT8, cap // 4, 4)) == -4                 # the payloads alone fill it: no room for scales
+    assert call(ring_of(B.NONE, cap, 1)) == -4
+    assert call(ring_of(B.TRUNC16, 0, 4)) == 0                        # empty vector: nothing to do
+    assert L.pipesgd_allreduce_direct_static(None, None) == -1
+    assert call(ring_of(7, 4096, 4)) == -3
+
+
 def test_product_does_not_import_the_oracle():
     pkg = os.path.join(ROOT, "paper_1811_03619_amd")
     for dirpath, _, files in os.walk(pkg):
