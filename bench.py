@@ -72,11 +72,16 @@ def bytes_model(mode: int, n: int, p: int, momentum: bool, fused: bool = False, 
             "total": first + rs + ag + upd}
 
 
+INFINITY_CACHE_BYTES = 256 * 2 ** 20   # MI355X memory-side cache
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--repeats", type=int, default=5,
+                    help="the block of --steps iterations is timed this many times; ms_per_step is the median block")
     ap.add_argument("--config", type=int, default=3, help="workload 1..5 (3 = AlexNet-shaped, 61M, the headline)")
     ap.add_argument("--mode", type=int, default=None, help="override compression mode 0/1/2")
     ap.add_argument("--schedule", choices=["stepwise", "fused", "one-launch", "direct", "halving-doubling"],
@@ -87,15 +92,18 @@ def main() -> int:
     ap.add_argument("--lr", type=float, default=0.01)
     ap.add_argument("--momentum", type=float, default=None)
     ap.add_argument("--seed", type=int, default=1)
-    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle timing (0 = skip)")
-    ap.add_argument("--phases", action="store_true", help="also time each phase separately")
+    ap.add_argument("--cpu-seconds", type=float, default=8.0,
+                    help="budget of each of the two oracle timings, one thread and all cores (0 = skip)")
+    ap.add_argument("--phases", action="store_true",
+                    help="also time each phase separately and run the memory-stream probes the update is measured against")
     ap.add_argument("--graph", action="store_true",
                     help="replay the iterations from a captured HIP graph (two iterations per replay); "
                          "the update kernel is then not bracketed by events, so roofline.achieved is null")
-    ap.add_argument("--two-streams", action="store_true",
-                    help="run the iterations through the library's two-stream runtime (Algorithm 1's two threads: the "
-                         "AllReduce on one stream, the update on the other); the update kernel is then not bracketed "
-                         "by events, so roofline.achieved is null")
+    ap.add_argument("--streams", choices=["auto", "1", "2"], default="auto",
+                    help="1: AllReduce and update back to back on one stream.  2: through the library's two-stream "
+                         "runtime (Algorithm 1's two threads: the AllReduce on one stream, the update on the other).  "
+                         "auto: 2 for bucketed workloads (many short launches, which the update then hides), else 1")
+    ap.add_argument("--two-streams", action="store_true", help="same as --streams 2")
     ap.add_argument("--no-stagger", action="store_true",
                     help="place every buffer at the start of a 4 KiB page instead of staggering them by multiples of "
                          "256 bytes (for comparison)")
@@ -110,6 +118,9 @@ def main() -> int:
     if args.gpus != 1:
         print("bench.py: this build runs the K simulated workers on ONE GPU; --gpus must be 1 "
               "(no multi-GPU path exists in this repository)", file=sys.stderr)
+        return 2
+    if args.repeats < 1 or args.steps < 1:
+        print("bench.py: --steps and --repeats must be at least 1", file=sys.stderr)
         return 2
 
     import numpy as np
@@ -137,6 +148,13 @@ def main() -> int:
     else:
         offs, n = list(np.cumsum([0] + numels[:-1])), int(sum(numels))
 
+    streams = args.streams
+    if args.two_streams:
+        streams = "2"
+    if streams == "auto":
+        streams = "2" if (buckets and schedule in (B.STEPWISE, B.FUSED) and not args.graph) else "1"
+    two_streams = streams == "2"
+
     def host_gradient(r: int) -> np.ndarray:
         flat = np.zeros(n, dtype=np.float32)
         for t, o in zip(W.gradient_tensors(cfg, r, args.seed), offs):
@@ -153,70 +171,95 @@ def main() -> int:
     sim.set_model(w0)
     torch.cuda.synchronize()
 
-    for _ in range(args.warmup):
-        sim.iteration()
-    torch.cuda.synchronize()
-
-    # ---- timed region: exactly `steps` iterations; the update launch of every
-    # iteration is bracketed by events on the launch stream for the roofline.
-    upd_ms = None
-    if args.two_streams:
+    # ---- one timed block = exactly `steps` iterations; returns wall seconds and the durations (ms) of the
+    # update launches in it, each bracketed by HIP events on the stream it is launched on
+    rt = None
+    graph = None
+    if two_streams:
         if schedule not in (B.STEPWISE, B.FUSED) or args.graph:
-            print("bench.py: --two-streams takes the stepwise or fused schedule, without --graph", file=sys.stderr)
+            print("bench.py: --streams 2 takes the stepwise or fused schedule, without --graph", file=sys.stderr)
             return 2
         rt = B.Runtime()
 
-        def run(k):
+        def block(k, timed=True):
             for _ in range(k):
                 cur = (sim.t + 1) % 2
                 rt.iteration(sim.rings[cur], sim.updates[1 - cur], sim.updates[cur], schedule, 2, sim.lr, sim.momentum,
-                             sim.grad_scale)
+                             sim.grad_scale, time_update=timed)
                 sim.t += 1
-        run(4)
-        rt.sync()
-        start_ev, stop_ev = None, None
-        t_begin = time.perf_counter()
-        run(args.steps)
-        rt.sync()
-        wall_s = time.perf_counter() - t_begin
-        rt.close()
+
+        timed_blocks = [0]
+
+        def run_block(k):
+            # the timing events cost a few microseconds per iteration on this path, so only the first block
+            # carries them; ms_per_step, the median block, is then a block without them
+            first = timed_blocks[0] == 0
+            timed_blocks[0] += 1
+            rt.update_time()                                   # forget what was recorded before
+            t_begin = time.perf_counter()
+            block(k, timed=first)
+            rt.sync()
+            wall = time.perf_counter() - t_begin
+            total_ms, launches = rt.update_time()
+            return wall, ([total_ms / launches] * launches if launches else [])
     elif args.graph:
-        if args.steps % 2 or sim.t % 2:
+        if args.steps % 2 or args.warmup % 2:
             print("bench.py: --graph replays pairs of iterations: use even --steps and --warmup", file=sys.stderr)
             return 2
+
+        def block(k, timed=True):
+            if graph is None:
+                for _ in range(k):
+                    sim.iteration()
+            else:
+                for _ in range(k // 2):
+                    graph.replay()
+
+        def run_block(k):
+            torch.cuda.synchronize()
+            t_begin = time.perf_counter()
+            block(k)
+            torch.cuda.synchronize()
+            return time.perf_counter() - t_begin, []
+    else:
+        def block(k, timed=True):
+            for _ in range(k):
+                sim.iteration()
+
+        def run_block(k):
+            ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(k)]
+            torch.cuda.synchronize()
+            t_begin = time.perf_counter()
+            if schedule == B.ONE_LAUNCH:
+                for _ in range(k):
+                    sim.iteration()
+            else:
+                for i in range(k):
+                    cur = sim.allreduce()
+                    ev[i][0].record()
+                    sim.update_from(1 - cur)
+                    ev[i][1].record()
+                    sim.t += 1
+            torch.cuda.synchronize()
+            wall = time.perf_counter() - t_begin
+            return wall, ([a.elapsed_time(b) for a, b in ev] if schedule != B.ONE_LAUNCH else [])
+
+    block(args.warmup, timed=False)
+    (rt.sync() if rt else torch.cuda.synchronize())
+    if args.graph:
         graph = sim.capture_pair()
         graph.replay()
         torch.cuda.synchronize()
-        start_ev, stop_ev = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        t_begin = time.perf_counter()
-        start_ev.record()
-        for _ in range(args.steps // 2):
-            graph.replay()
-        stop_ev.record()
-        torch.cuda.synchronize()
-        wall_s = time.perf_counter() - t_begin
-    else:
-        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-        start_ev, stop_ev = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
-        t_begin = time.perf_counter()
-        start_ev.record()
-        if schedule == B.ONE_LAUNCH:
-            for i in range(args.steps):
-                sim.iteration()
-        else:
-            for i in range(args.steps):
-                cur = sim.allreduce()
-                ev[i][0].record()
-                sim.update_from(1 - cur)
-                ev[i][1].record()
-                sim.t += 1
-        stop_ev.record()
-        torch.cuda.synchronize()
-        wall_s = time.perf_counter() - t_begin
-        upd_ms = float(np.mean([a.elapsed_time(b) for a, b in ev])) if schedule != B.ONE_LAUNCH else None
-    ms_per_step = wall_s * 1e3 / args.steps
-    gpu_ms_per_step = start_ev.elapsed_time(stop_ev) / args.steps if start_ev is not None else ms_per_step
+
+    block_ms, upd_all = [], []
+    for _ in range(args.repeats):
+        wall_s, upd = run_block(args.steps)
+        block_ms.append(wall_s * 1e3 / args.steps)
+        upd_all += upd
+    ms_per_step = float(np.median(block_ms))
+    upd_ms = float(np.mean(upd_all)) if upd_all else None
+    if rt is not None:
+        rt.close()
 
     n_true = int(sum(numels))          # bucket padding is processed but is not part of the model
     model = bytes_model(mode, n_true, p, momentum != 0.0, fused=(schedule in (B.FUSED, B.ONE_LAUNCH)), direct=(schedule == B.DIRECT),
@@ -224,7 +267,23 @@ def main() -> int:
     value = model["total"] / (ms_per_step * 1e-3) / 1e9
     upd_gbs = model["update"] / (upd_ms * 1e-3) / 1e9 if upd_ms else None
 
-    traffic = committed_traffic(cfg, ["none", "trunc16", "quant8"][mode])
+    mode_name = ["none", "trunc16", "quant8"][mode]
+    traffic, traffic_note = committed_traffic(cfg, mode_name, B.get_launch_config(B.K_UPDATE, mode))
+
+    cb = payload_bytes_per_elem(mode)
+    working_set = p * n * (4 + 2 * cb + 8)              # gradients, two slot sets, w and v of every worker
+    round_payload = n * cb                               # what one ring round writes (p blocks of n/p) and the next reads
+    cache = {
+        "infinity_cache_bytes": INFINITY_CACHE_BYTES, "working_set_bytes": int(working_set),
+        "ring_round_payload_bytes": int(round_payload),
+        "whole_iteration": bool(working_set <= INFINITY_CACHE_BYTES),
+        "allreduce_rounds": bool(round_payload <= INFINITY_CACHE_BYTES),
+        "note": ("the whole working set fits the memory-side cache: the figures are not HBM figures"
+                 if working_set <= INFINITY_CACHE_BYTES else
+                 "a ring round's payloads fit the memory-side cache, so the next round may read them from there: "
+                 "the AllReduce part of `value` is cache-assisted; the update streams its operands once and is not"
+                 if round_payload <= INFINITY_CACHE_BYTES else "nothing on this path fits the memory-side cache"),
+    }
 
     out = {
         "metric": "aggregation+update GB/s (fraction of HBM peak) and iters/s at K=4, 61M params",
@@ -243,26 +302,43 @@ def main() -> int:
             "workload": f"config{cfg}:{W.CONFIG_NAMES[cfg]}", "workers": p, "elements_per_worker": n_true,
             "packed_elements_per_worker": n,
             "tensors": len(specs), "buckets": len(buckets) if buckets else 1,
-            "compression": ["none", "trunc16", "quant8"][mode], "momentum": momentum, "lr": args.lr,
-            "pipeline_width": 2, "schedule": args.schedule, "hip_graph": bool(args.graph), "two_streams": bool(args.two_streams), "staggered_buffers": not args.no_stagger, "seed": args.seed,
+            "compression": mode_name, "momentum": momentum, "lr": args.lr,
+            "pipeline_width": 2, "schedule": args.schedule, "hip_graph": bool(args.graph),
+            "streams": 2 if two_streams else 1, "staggered_buffers": not args.no_stagger, "seed": args.seed,
         },
+        "repeats": args.repeats,
+        "ms_per_step_min": round(min(block_ms), 5),
+        "ms_per_step_max": round(max(block_ms), 5),
+        "timing": f"wall clock around each of {args.repeats} blocks of {args.steps} iterations (synchronised on both "
+                  f"sides); ms_per_step is the median block, min and max are the fastest and slowest block",
         "iters_per_s": round(1e3 / ms_per_step, 2),
         "hbm_peak_fraction": round(value / HBM_PEAK_GBS, 4),
-        "gpu_ms_per_step": round(gpu_ms_per_step, 5),
+        "cache_assisted": cache,
         "bytes_per_iter": {k: int(v) for k, v in model.items()},
         "roofline": {
             "kernel": "update_kernel (decompress + momentum-SGD, all replicas, one launch)",
             "bound": "hbm", "achieved": round(upd_gbs, 2) if upd_gbs else None, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": round(upd_gbs / HBM_PEAK_GBS, 4) if upd_gbs else None, "traffic": traffic,
-            "launch_ms": round(upd_ms, 5) if upd_ms else None, "algorithmic_bytes_per_launch": int(model["update"]),
+            "traffic_note": traffic_note,
+            "launch_ms": round(upd_ms, 5) if upd_ms else None, "launches_timed": len(upd_all),
+            "algorithmic_bytes_per_launch": int(model["update"]),
+            "overlapped": bool(two_streams),
+            "launch_geometry": dict(zip(("threads", "quads", "lds_bytes"), B.get_launch_config(B.K_UPDATE, mode))),
         },
+        "kernel_sources_sha256": kernel_sources_sha256(),
         "input_generation_s": round(gen_s, 2),
     }
+    if two_streams:
+        out["roofline"]["note"] = ("the update runs beside the AllReduce launches of the other stream and shares the "
+                                   "memory bandwidth with them, so its own duration is longer than alone "
+                                   "(--streams 1 times it alone)")
 
     if args.phases:
         out["phases_ms"] = time_phases(sim, B, torch, np)
     if buckets:
-        out["bucketing"] = time_packing(sim, B, torch, np, numels, offs, n)
+        out["bucketing"] = time_packing(sim, B, torch, np, numels, offs, n, model["total"])
+    if args.phases:
+        out["ceiling"] = stream_ceiling(sim, B, torch, np)         # last: the probes overwrite w and v
 
     if args.calib_copy > 0:
         dst = torch.empty_like(sim.g_local[0])
@@ -294,10 +370,12 @@ def main() -> int:
     return 0
 
 
-def time_packing(sim, B, torch, np, numels, offs, n, reps: int = 20):
-    """Step a0, timed on its own (it is not part of the timed iteration): gather
-    every worker's per-layer gradient tensors into its packed buffer, one launch
-    for all tensors of all workers, and the scatter back."""
+def time_packing(sim, B, torch, np, numels, offs, n, iter_bytes, reps: int = 20):
+    """Step a0, timed on its own (it is NOT part of the timed iteration, whose
+    gradients already sit in the packed buffers): gather every worker's
+    per-layer gradient tensors into its packed buffer, one launch for all
+    tensors of all workers, and the scatter back.  Also the iteration with one
+    gather launch put in front of every AllReduce."""
     p, dev = sim.p, sim.device
     starts = np.cumsum([0] + [ne + (-ne) % 4 for ne in numels])        # 16-byte aligned tensors in one arena
     arenas = [torch.randn(int(starts[-1]), device=dev) * 1e-3 for _ in range(p)]
@@ -325,22 +403,71 @@ def time_packing(sim, B, torch, np, numels, offs, n, reps: int = 20):
     pack_ms = timed(lambda: B.pack(tab_dev, len(ne), total))
     unpack_ms = timed(lambda: B.unpack(tab_dev, len(ne), total))
     moved = 8.0 * p * float(sum(numels))
-    return {"tensors": len(numels), "workers": p, "launches": 1, "pack_ms": round(pack_ms, 5),
-            "unpack_ms": round(unpack_ms, 5), "pack_GBps": round(moved / pack_ms / 1e6, 1),
-            "unpack_GBps": round(moved / unpack_ms / 1e6, 1)}
+
+    # the whole iteration with the gather in it: gather on the communication stream in front of the AllReduce,
+    # the update beside both on the other stream
+    res = {"tensors": len(numels), "workers": p, "launches": 1, "pack_ms": round(pack_ms, 5),
+           "unpack_ms": round(unpack_ms, 5), "pack_GBps": round(moved / pack_ms / 1e6, 1),
+           "unpack_GBps": round(moved / unpack_ms / 1e6, 1), "included_in_value": False}
+    if sim.schedule in (B.STEPWISE, B.FUSED):
+        rt = B.Runtime()
+        comm = rt.stream(1)
+
+        def run(k):
+            for _ in range(k):
+                cur = (sim.t + 1) % 2
+                B.pack(tab_dev, len(ne), total, stream=comm)
+                rt.iteration(sim.rings[cur], sim.updates[1 - cur], sim.updates[cur], sim.schedule, 2, sim.lr,
+                             sim.momentum, sim.grad_scale)
+                sim.t += 1
+        run(6)
+        rt.sync()
+        blocks = []
+        for _ in range(5):
+            t0 = time.perf_counter()
+            run(100)
+            rt.sync()
+            blocks.append((time.perf_counter() - t0) * 10.0)           # ms per iteration
+        rt.close()
+        ms = float(np.median(blocks))
+        res["iteration_with_pack_ms"] = round(ms, 5)
+        res["iteration_with_pack_GBps"] = round((iter_bytes + moved) / ms / 1e6, 1)
+    return res
 
 
-def committed_traffic(cfg: int, mode_name: str):
+def kernel_sources_sha256() -> str:
+    """Hash of the kernel sources: a counter summary under profiles/ holds for the code it was taken with."""
+    import hashlib
+    from paper_1811_03619_amd import buildlib
+    h = hashlib.sha256()
+    for name in ("pipesgd_kernels.hip", "pipesgd_device.hpp"):
+        h.update(open(os.path.join(buildlib.CSRC, name), "rb").read())
+    return h.hexdigest()
+
+
+def committed_traffic(cfg: int, mode_name: str, update_geometry):
     """HBM-side bytes per update launch from the committed rocprofv3 --pmc
     summary of this workload (FETCH_SIZE and WRITE_SIZE runs, scaled by a copy
-    kernel of known size); None if no summary exists for it."""
+    kernel of known size) -- only if that summary was taken with the kernel
+    sources and the update launch geometry of this run; otherwise None and the
+    reason."""
     import glob
     import re
-    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", f"pmc_traffic_config{cfg}_*{mode_name}*.txt"))):
-        m = re.search(r"^update_kernel traffic_bytes_per_launch = (\d+)", open(path).read(), flags=re.M)
-        if m:
-            return int(m.group(1))
-    return None
+    paths = sorted(glob.glob(os.path.join(ROOT, "profiles", f"pmc_traffic_config{cfg}_*{mode_name}*.txt")))
+    if not paths:
+        return None, "no counter summary under profiles/ for this workload"
+    text = open(paths[0]).read()
+    m = re.search(r"^update_kernel traffic_bytes_per_launch = (\d+)", text, flags=re.M)
+    g = re.search(r"^update_kernel launch_config = threads (\d+) quads (\d+) lds_bytes (\d+)", text, flags=re.M)
+    h = re.search(r"^kernel_sources_sha256 = ([0-9a-f]{64})", text, flags=re.M)
+    name = os.path.basename(paths[0])
+    if not (m and g and h):
+        return None, f"{name} does not say which sources and launch geometry it was taken with"
+    if tuple(int(x) for x in g.groups()) != tuple(update_geometry):
+        return None, f"{name} was taken with update geometry {g.groups()}, this run uses {tuple(update_geometry)}"
+    if h.group(1) != kernel_sources_sha256():
+        return None, f"{name} was taken with other kernel sources than this tree's"
+    return int(m.group(1)), f"from {name} (same kernel sources, same launch geometry)"
 
 
 def time_phases(sim, B, torch, np, reps: int = 20):
@@ -381,6 +508,52 @@ def time_phases(sim, B, torch, np, reps: int = 20):
                        sim.v[:1] if sim.momentum != 0.0 else None)
     res["update_one_replica"] = timed(lambda: B.apply_update_multi(sim.mode, one, sim.n, sim.lr, sim.momentum,
                                                                    sim.grad_scale))
+    return res
+
+
+def stream_ceiling(sim, B, torch, np, reps: int = 15):
+    """What the memory system sustains for the update's access mix: the library's
+    stream probes (the update's loads and stores over the update's own buffers,
+    grid and cache policy, no arithmetic) in a handful of launch geometries, best
+    of each.  Overwrites w and v, so it runs last."""
+    ua = sim.updates[1]
+    p, n, mode = sim.p, sim.n, sim.mode
+    cb = payload_bytes_per_elem(mode)
+
+    def timed(fn):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(reps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(); fn(); b.record()
+            torch.cuda.synchronize()
+            ts.append(a.elapsed_time(b))
+        return float(np.median(ts))
+
+    geos = [(64, 4, 53248), (64, 4, 65536), (128, 2, 65536), (256, 1, 53248), (256, 1, 65536), (256, 1, 0),
+            (256, 4, 0), (512, 2, 0), (256, 2, 53248)]
+    kinds = {"read_only": (B.PROBE_READ, p * n * (cb + 8.0)), "write_only": (B.PROBE_WRITE, p * n * 8.0),
+             "mixed_in_place": (B.PROBE_MIXED, p * n * (cb + 16.0)), "copy": (B.PROBE_COPY, p * n * 8.0)}
+    res = {"what": "pipesgd_probe_stream over the update's buffers (all replicas), best launch geometry of each kind",
+           "unit": "GB/s"}
+    for name, (kind, nbytes) in kinds.items():
+        best = None
+        for (t, q, lds) in geos:
+            ms = timed(lambda: B.probe_stream(kind, mode, ua, n, t, q, lds))
+            if best is None or ms < best[0]:
+                best = (ms, (t, q, lds))
+        res[name] = {"GBps": round(nbytes / best[0] / 1e6, 1), "ms": round(best[0], 5), "bytes": int(nbytes),
+                     "geometry": list(best[1])}
+    upd_bytes = p * n * (cb + 16.0)
+    t, q, lds = B.get_launch_config(B.K_UPDATE, mode)
+    upd_ms = timed(lambda: sim.update_from(1))
+    res["update_kernel"] = {"GBps": round(upd_bytes / upd_ms / 1e6, 1), "ms": round(upd_ms, 5), "geometry": [t, q, lds]}
+    res["update_over_mixed_probe"] = round(res["update_kernel"]["GBps"] / res["mixed_in_place"]["GBps"], 4)
+    # reads and writes take turns on the memory bus: the time of a mix is at least the sum of its parts' times
+    rd, wr = res["read_only"]["GBps"], res["write_only"]["GBps"]
+    res["no_interference_bound_GBps"] = round((cb + 16.0) / ((cb + 8.0) / rd + 8.0 / wr), 1)
     return res
 
 
@@ -611,30 +784,71 @@ def study_two_thread_runtime(sim, B, torch, np, schedule, iters: int = 30):
 
 
 def cpu_baseline(mode, grads, w0, p, lr, momentum, buckets, bytes_total, budget_s):
-    """The oracle as it stands, one host thread, same inputs, same iteration
-    (AllReduce of p workers + update of p replicas)."""
+    """The oracle as it stands, same inputs, same iteration (AllReduce of p
+    workers + update of p replicas).  `value` is the oracle on ONE host thread
+    (it is single-threaded as written).  `all_cores` runs the same oracle calls
+    on every host core at once: the vector is cut into as many 4096-aligned slabs
+    as there are threads and each thread runs the oracle's AllReduce and update on
+    its slab (the calls release the interpreter lock).  Same arithmetic per element
+    and the same bytes; only the assignment of elements to ring blocks differs from
+    the single call, which timing does not care about."""
+    import concurrent.futures as cf
+
     import numpy as np
 
     import oracle
     n = w0.size
-    ws = [w0.copy() for _ in range(p)]
-    vs = [np.zeros(n, np.float32) for _ in range(p)]
-    slot = None
-    iters, t0 = 0, time.perf_counter()
-    while True:
-        A = oracle.allreduce_bucketed(mode, grads, buckets) if buckets else oracle.allreduce(mode, grads)
-        use = A if slot is None else slot           # same work either way; first pass has no earlier slot
+
+    def one_iteration(lo, hi, ws, vs, slot):
+        g = [x[lo:hi] for x in grads]
+        if buckets:
+            bl = [(max(st, lo) - lo, min(st + nb, hi) - max(st, lo)) for st, nb in buckets if st < hi and st + nb > lo]
+            A = oracle.allreduce_bucketed(mode, g, bl)
+        else:
+            A = oracle.allreduce(mode, g)
+        use = A if slot is None else slot            # same work either way; the first pass has no earlier slot
         for r in range(p):
             oracle.sgd_update(mode, use[r][0], use[r][1], ws[r], vs[r] if momentum else None, lr, momentum, 1.0)
-        slot = A
-        iters += 1
-        el = time.perf_counter() - t0
-        if el >= budget_s or (iters >= 1 and el * (iters + 1) / iters > 2.5 * budget_s):
-            break
-    s_per_iter = el / iters
-    return {"value": round(bytes_total / s_per_iter / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
-            "sample": f"{iters} full iteration(s) of the same workload (all {p} workers, all {n} elements)",
-            "s_per_iter": round(s_per_iter, 4), "iters_per_s": round(1.0 / s_per_iter, 4)}
+        return A
+
+    def run(threads):
+        if buckets and threads > 1:
+            # whole buckets per thread: a new slab starts at the first bucket past each equal share of the elements
+            cuts = [0]
+            for st, nb in buckets:
+                if st > 0 and st >= n * len(cuts) / threads and len(cuts) < threads:
+                    cuts.append(st)
+            cuts.append(n)
+        else:
+            step = -(-n // threads // 4096) * 4096 if threads > 1 else n
+            cuts = list(range(0, n, max(step, 4096))) + [n]
+        slabs = [(a, b) for a, b in zip(cuts[:-1], cuts[1:]) if b > a]
+        state = []
+        for lo, hi in slabs:
+            state.append([[w0[lo:hi].copy() for _ in range(p)], [np.zeros(hi - lo, np.float32) for _ in range(p)], None])
+        iters, t0 = 0, time.perf_counter()
+        with cf.ThreadPoolExecutor(max_workers=len(slabs)) as pool:
+            while True:
+                futs = [pool.submit(one_iteration, lo, hi, st[0], st[1], st[2]) for (lo, hi), st in zip(slabs, state)]
+                for st, f in zip(state, futs):
+                    st[2] = f.result()
+                iters += 1
+                el = time.perf_counter() - t0
+                if el >= budget_s or el * (iters + 1) / iters > 2.5 * budget_s:
+                    break
+        return el / iters, iters, len(slabs)
+
+    s1, it1, _ = run(1)
+    cores = max(1, min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16") or 16)))
+    sN, itN, used = run(cores) if cores > 1 else (s1, it1, 1)
+    return {"value": round(bytes_total / s1 / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": f"{it1} full iteration(s) of the same workload (all {p} workers, all {n} elements)",
+            "s_per_iter": round(s1, 4), "iters_per_s": round(1.0 / s1, 4),
+            "all_cores": {"value": round(bytes_total / sN / 1e9, 3), "unit": "GB/s", "cores": used, "kind": "oracle",
+                          "sample": f"{itN} full iteration(s); the vector cut into {used} slabs, one oracle call "
+                                    f"sequence per slab and thread",
+                          "s_per_iter": round(sN, 4), "iters_per_s": round(1.0 / sN, 4),
+                          "host_cpus_visible": os.cpu_count()}}
 
 
 if __name__ == "__main__":

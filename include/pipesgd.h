@@ -417,6 +417,8 @@ int pipesgd_unpack(const pipesgd_segment *segments, uint64_t num, uint64_t total
  * the same iteration can be issued again. */
 typedef struct pipesgd_runtime pipesgd_runtime;
 
+#define PIPESGD_RT_TIME_UPDATE 1
+
 typedef struct pipesgd_runtime_iter {
     const pipesgd_ring *ring;            /* AllReduce of this iteration (HOST struct) */
     int32_t  schedule;                   /* PIPESGD_STEPWISE / PIPESGD_FUSED */
@@ -428,7 +430,8 @@ typedef struct pipesgd_runtime_iter {
                                             the payloads would spend on a network (Eq. 5's alpha and beta terms);
                                             it occupies one wavefront and no memory bandwidth (0 = none) */
     float    lr, momentum, grad_scale;
-    int32_t  reserved;                   /* must be 0 */
+    int32_t  flags;                      /* 0, or PIPESGD_RT_TIME_UPDATE: bracket this iteration's update launch with
+                                            timing events on the compute stream (see pipesgd_runtime_update_time) */
     const void  *const *stale_g_sum_c;   /* HOST arrays of DEVICE pointers, as for pipesgd_apply_update_multi */
     const float *const *stale_scales;
     const void  *const *fresh_g_sum_c;   /* width 1 only */
@@ -441,6 +444,12 @@ int   pipesgd_runtime_create(pipesgd_runtime **out);
 void  pipesgd_runtime_destroy(pipesgd_runtime *rt);       /* synchronises both streams first */
 int   pipesgd_runtime_iteration(pipesgd_runtime *rt, const pipesgd_runtime_iter *it);
 int   pipesgd_runtime_sync(pipesgd_runtime *rt);          /* host waits for both streams */
+/* Waits for the compute stream, then returns the summed duration (milliseconds,
+ * HIP events on the compute stream) and the number of the update launches that
+ * were timed (PIPESGD_RT_TIME_UPDATE) since the previous call, and starts anew.
+ * While the AllReduce runs beside it on the other stream an update takes longer
+ * than alone: both draw on the same memory bandwidth. */
+int   pipesgd_runtime_update_time(pipesgd_runtime *rt, double *total_ms, uint64_t *launches);
 void *pipesgd_runtime_stream(pipesgd_runtime *rt, int which);   /* 0 = compute, 1 = comm: a hipStream_t */
 
 /* The stand-in for forward + backward: `workgroups` workgroups of 64 threads
@@ -490,6 +499,28 @@ double pipesgd_model_scaling_efficiency(double l_up, double l_comp, double l_com
 #define PIPESGD_K_DECOMPRESS      6
 int pipesgd_set_launch_config(int kernel, int mode, int threads, int quads, int lds_bytes);
 int pipesgd_get_launch_config(int kernel, int mode, int *threads, int *quads, int *lds_bytes);
+
+/* ------------------------------------------------------------ measurement -- */
+
+/* Not part of the method: the update's memory streams with the arithmetic taken
+ * out, to find what the memory system sustains for that access mix (the ceiling
+ * the update kernel is measured against).  Runs over the update's own buffers
+ * and grid (replicas x whole units of n; a ragged tail is left out), with the
+ * update's cache policy, in the given launch geometry (see "tuning").
+ *   PIPESGD_PROBE_READ   loads slot, w and v; stores nothing
+ *   PIPESGD_PROBE_WRITE  stores finite bit patterns into w and v; loads nothing
+ *   PIPESGD_PROBE_MIXED  loads slot, w and v; stores v's values into w and w's
+ *                        into v: the update's bytes (TRUNC16: 10 read, 8 written
+ *                        per element) without decode or multiply-adds
+ *   PIPESGD_PROBE_COPY   loads w, stores it into v (the usual 1 : 1 copy figure)
+ * Arguments as for pipesgd_apply_update_multi (v is always needed).  WRITE, MIXED
+ * and COPY overwrite w and/or v. */
+#define PIPESGD_PROBE_READ   0
+#define PIPESGD_PROBE_WRITE  1
+#define PIPESGD_PROBE_MIXED  2
+#define PIPESGD_PROBE_COPY   3
+int pipesgd_probe_stream(int kind, int mode, int replicas, const void *const *g_sum_c, float *const *w,
+                         float *const *v, uint64_t n, int threads, int quads, int lds_bytes, void *stream);
 
 #ifdef __cplusplus
 }

@@ -31,12 +31,13 @@ EXPORTS = [
     "pipesgd_set_launch_config", "pipesgd_get_launch_config",
     "pipesgd_overlap_create", "pipesgd_overlap_destroy", "pipesgd_allreduce_pipelined",
     "pipesgd_runtime_create", "pipesgd_runtime_destroy", "pipesgd_runtime_iteration", "pipesgd_runtime_sync",
-    "pipesgd_runtime_stream", "pipesgd_synthetic_compute",
+    "pipesgd_runtime_stream", "pipesgd_runtime_update_time", "pipesgd_synthetic_compute",
     "pipesgd_model_sync_time", "pipesgd_model_pipe_ideal_time", "pipesgd_model_pipe_time",
     "pipesgd_model_ring_comm_time", "pipesgd_model_scaling_efficiency", "pipesgd_iteration_fused", "pipesgd_allreduce_direct",
     "pipesgd_allreduce_halving_doubling", "pipesgd_workspace_bytes", "pipesgd_placement_offset",
-    "pipesgd_allreduce_direct_static",
+    "pipesgd_allreduce_direct_static", "pipesgd_probe_stream",
 ]
+PROBE_READ, PROBE_WRITE, PROBE_MIXED, PROBE_COPY = range(4)
 STATIC_SCRATCH_BYTES = 32 << 20
 K_FIRST_SEND, K_REDUCE_SCATTER, K_ALLGATHER, K_FUSED, K_UPDATE, K_COMPRESS, K_DECOMPRESS = range(7)
 
@@ -63,12 +64,15 @@ class RingStruct(C.Structure):
     ]
 
 
+RT_TIME_UPDATE = 1
+
+
 class RuntimeIter(C.Structure):
     _fields_ = [
         ("ring", C.POINTER(RingStruct)),
         ("schedule", C.c_int32), ("width", C.c_int32), ("replicas", C.c_int32), ("compute_workgroups", C.c_int32),
         ("compute_us", C.c_float), ("wire_us", C.c_float), ("lr", C.c_float), ("momentum", C.c_float),
-        ("grad_scale", C.c_float), ("reserved", C.c_int32),
+        ("grad_scale", C.c_float), ("flags", C.c_int32),
         ("stale_g_sum_c", C.c_void_p), ("stale_scales", C.c_void_p),
         ("fresh_g_sum_c", C.c_void_p), ("fresh_scales", C.c_void_p),
         ("w", C.c_void_p), ("v", C.c_void_p),
@@ -152,6 +156,8 @@ def lib():
     L.pipesgd_runtime_iteration.argtypes = [vp, C.POINTER(RuntimeIter)]
     L.pipesgd_runtime_sync.restype = i32
     L.pipesgd_runtime_sync.argtypes = [vp]
+    L.pipesgd_runtime_update_time.restype = i32
+    L.pipesgd_runtime_update_time.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_uint64)]
     L.pipesgd_runtime_stream.restype = vp
     L.pipesgd_runtime_stream.argtypes = [vp, i32]
     L.pipesgd_synthetic_compute.restype = i32
@@ -167,6 +173,8 @@ def lib():
     L.pipesgd_allreduce_direct.argtypes = [C.POINTER(RingStruct), C.POINTER(Workspace), vp]
     L.pipesgd_allreduce_direct_static.restype = i32
     L.pipesgd_allreduce_direct_static.argtypes = [C.POINTER(RingStruct), vp]
+    L.pipesgd_probe_stream.restype = i32
+    L.pipesgd_probe_stream.argtypes = [i32, i32, i32, vp, vp, vp, u64, i32, i32, i32, vp]
     L.pipesgd_placement_offset.restype = u64
     L.pipesgd_placement_offset.argtypes = [i32, i32, i32]
     L.pipesgd_workspace_bytes.restype = i32
@@ -388,11 +396,12 @@ class Runtime:
 
     def iteration(self, ring: RingStruct, stale: "UpdateArgs", fresh: Optional["UpdateArgs"], schedule: int,
                   width: int, lr: float, momentum: float, grad_scale: float = 1.0, compute_us: float = 0.0,
-                  compute_workgroups: int = 1, wire_us: float = 0.0) -> None:
+                  compute_workgroups: int = 1, wire_us: float = 0.0, time_update: bool = False) -> None:
         it = RuntimeIter()
         it.ring = C.pointer(ring)
         it.schedule, it.width, it.replicas, it.compute_workgroups = schedule, width, stale.replicas, compute_workgroups
-        it.compute_us, it.wire_us, it.lr, it.momentum, it.grad_scale, it.reserved = compute_us, wire_us, lr, momentum, grad_scale, 0
+        it.compute_us, it.wire_us, it.lr, it.momentum, it.grad_scale = compute_us, wire_us, lr, momentum, grad_scale
+        it.flags = RT_TIME_UPDATE if time_update else 0
         it.stale_g_sum_c = C.cast(stale.g_sum_c, C.c_void_p)
         it.stale_scales = C.cast(stale.scales, C.c_void_p) if stale.scales is not None else None
         if fresh is not None:
@@ -404,6 +413,12 @@ class Runtime:
 
     def sync(self) -> None:
         check(lib().pipesgd_runtime_sync(self.handle), "pipesgd_runtime_sync")
+
+    def update_time(self) -> Tuple[float, int]:
+        """(summed milliseconds, count) of the update launches timed since the last call."""
+        ms, k = C.c_double(), C.c_uint64()
+        check(lib().pipesgd_runtime_update_time(self.handle, C.byref(ms), C.byref(k)), "pipesgd_runtime_update_time")
+        return float(ms.value), int(k.value)
 
     def stream(self, which: int) -> int:
         return lib().pipesgd_runtime_stream(self.handle, which)
@@ -447,6 +462,13 @@ def apply_update_multi(mode: int, args: UpdateArgs, n: int, lr: float, momentum:
     check(lib().pipesgd_apply_update_multi(mode, args.replicas, args.g_sum_c, args.scales, n, args.w, args.v,
                                            lr, momentum, grad_scale, _stream(stream)),
           "pipesgd_apply_update_multi")
+
+
+def probe_stream(kind: int, mode: int, args: UpdateArgs, n: int, threads: int, quads: int, lds_bytes: int = 0,
+                 stream=None) -> None:
+    """Measurement aid: the update's memory streams without its arithmetic (overwrites w / v)."""
+    check(lib().pipesgd_probe_stream(kind, mode, args.replicas, args.g_sum_c, args.w, args.v, n, threads, quads,
+                                     lds_bytes, _stream(stream)), "pipesgd_probe_stream")
 
 
 def set_launch_config(kernel: int, mode: int, threads: int, quads: int, lds_bytes: int = 0) -> None:

@@ -22,6 +22,17 @@ constexpr int kTileQuads = kTile / 4;
 constexpr int kMaxW = PIPESGD_MAX_WORKERS;
 constexpr int kMaxB = PIPESGD_MAX_BUCKETS;
 
+// Which quads of a unit a thread owns.  Strided (the default): quad i of thread t
+// is quad i*THREADS + t, so every load instruction of a wave covers one contiguous
+// run.  Lane-contiguous (build with -DPIPESGD_LANE_CONTIGUOUS=1): quad i of thread t
+// is quad t*QUADS + i, so a thread's 16-bit (QUADS = 2) or 8-bit (QUADS = 4) payload
+// is ONE 128-bit load, at the price of fp32 loads whose lanes sit 32 or 64 bytes
+// apart.  Measured slower on MI355X, so it is off; kept as a build option because
+// results do not depend on it (the parity tests pass with either).
+#ifndef PIPESGD_LANE_CONTIGUOUS
+#define PIPESGD_LANE_CONTIGUOUS 0
+#endif
+
 // Workgroup geometry.  kUnit elements per workgroup; kSplit units per tile.
 template <int THREADS, int QUADS> struct Geo {
     static constexpr int kThreads = THREADS;
@@ -30,7 +41,13 @@ template <int THREADS, int QUADS> struct Geo {
     static constexpr int kUnit = THREADS * QUADS * 4;
     static constexpr int kSplit = kTile / kUnit;
     static constexpr int kWaves = THREADS / 64;
+    static constexpr bool kContig = PIPESGD_LANE_CONTIGUOUS != 0;
     static_assert(THREADS % 64 == 0 && kUnit <= kTile && kTile % kUnit == 0, "geometry");
+    // index, within the unit, of the i-th quad this thread owns
+    __device__ static __forceinline__ uint32_t quad(int i)
+    {
+        return kContig ? threadIdx.x * QUADS + i : i * THREADS + threadIdx.x;
+    }
 };
 
 // ------------------------------------------------- streaming memory access --
@@ -277,9 +294,24 @@ template <> struct Codec<PIPESGD_QUANT8> {
     }
 };
 
+// Lane-contiguous layout: when a thread's QUADS consecutive quads of payload make
+// up exactly 16 bytes they travel as one 128-bit vector.
+template <class C, class G>
+constexpr bool kWide128 = G::kContig && sizeof(typename C::Raw) * G::kQuads == 16 && sizeof(typename C::Raw) < 16;
+
+template <class C> __device__ __forceinline__ void split128(const u32x4 &q, typename C::Raw *r)
+{
+    if constexpr (sizeof(typename C::Raw) == 8) { r[0] = typename C::Raw{q.x, q.y}; r[1] = typename C::Raw{q.z, q.w}; }
+    else { r[0] = q.x; r[1] = q.y; r[2] = q.z; r[3] = q.w; }
+}
+template <class C> __device__ __forceinline__ u32x4 join128(const typename C::Raw *r)
+{
+    if constexpr (sizeof(typename C::Raw) == 8) return u32x4{r[0].x, r[0].y, r[1].x, r[1].y};
+    else return u32x4{r[0], r[1], r[2], r[3]};
+}
+
 // ------------------------------------------------------- unit load / store --
-// x[4*QUADS] of a thread: x[4*i + e] = element 4*(i*THREADS + tid) + e of the
-// unit.  The *_full variants assume a whole, 16-byte aligned unit; the *_tail
+// x[4*QUADS] of a thread: x[4*i + e] = element 4*G::quad(i) + e of the unit.  The *_full variants assume a whole, 16-byte aligned unit; the *_tail
 // variants guard every element against `len` and fill the rest with zero.
 // FULL is a template parameter everywhere: a kernel decides once per workgroup
 // which body to run, so that in the full body nothing separates the loads and
@@ -291,7 +323,7 @@ __device__ __forceinline__ void load_f32_full(const float *base, float *x)
     const f32x4 *v = reinterpret_cast<const f32x4 *>(base);
     f32x4 r[G::kQuads];
 #pragma unroll
-    for (int i = 0; i < G::kQuads; ++i) r[i] = ld<NT>(v + i * G::kThreads + threadIdx.x);
+    for (int i = 0; i < G::kQuads; ++i) r[i] = ld<NT>(v + G::quad(i));
 #pragma unroll
     for (int i = 0; i < G::kQuads; ++i) { x[4 * i] = r[i].x; x[4 * i + 1] = r[i].y; x[4 * i + 2] = r[i].z; x[4 * i + 3] = r[i].w; }
 }
@@ -306,14 +338,14 @@ __device__ __forceinline__ void load_f32_tail(const float *base, uint32_t len, f
     for (int i = 0; i < G::kQuads; ++i)
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const uint32_t idx = 4 * (i * G::kThreads + threadIdx.x) + e;
+            const uint32_t idx = 4 * G::quad(i) + e;
             r[4 * i + e] = base[min(idx, len - 1)];
         }
 #pragma unroll
     for (int i = 0; i < G::kQuads; ++i)
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const uint32_t idx = 4 * (i * G::kThreads + threadIdx.x) + e;
+            const uint32_t idx = 4 * G::quad(i) + e;
             x[4 * i + e] = idx < len ? r[4 * i + e] : 0.0f;
         }
 }
@@ -329,13 +361,13 @@ __device__ __forceinline__ void store_f32(float *base, uint32_t len, const float
         f32x4 *v = reinterpret_cast<f32x4 *>(base);
 #pragma unroll
         for (int i = 0; i < G::kQuads; ++i)
-            st<NT>(v + i * G::kThreads + threadIdx.x, f32x4{x[4 * i], x[4 * i + 1], x[4 * i + 2], x[4 * i + 3]});
+            st<NT>(v + G::quad(i), f32x4{x[4 * i], x[4 * i + 1], x[4 * i + 2], x[4 * i + 3]});
     } else {
 #pragma unroll
         for (int i = 0; i < G::kQuads; ++i)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const uint32_t idx = 4 * (i * G::kThreads + threadIdx.x) + e;
+                const uint32_t idx = 4 * G::quad(i) + e;
                 if (idx < len) base[idx] = x[4 * i + e];
             }
     }
@@ -352,8 +384,14 @@ __device__ __forceinline__ void load_payload(const void *pay, uint64_t e0, uint3
         const typename C::Raw *v =
             reinterpret_cast<const typename C::Raw *>(static_cast<const char *>(pay) + e0 * C::kBytes);
         typename C::Raw r[G::kQuads];
+        if constexpr (kWide128<C, G>) {
+            // the thread's QUADS consecutive quads of payload are 16 bytes: one 128-bit load
+            const u32x4 q = ld<NT>(reinterpret_cast<const u32x4 *>(v) + threadIdx.x);
+            split128<C>(q, r);
+        } else {
 #pragma unroll
-        for (int i = 0; i < G::kQuads; ++i) r[i] = ld<NT>(v + i * G::kThreads + threadIdx.x);
+            for (int i = 0; i < G::kQuads; ++i) r[i] = ld<NT>(v + G::quad(i));
+        }
 #pragma unroll
         for (int i = 0; i < G::kQuads; ++i) C::decode(r[i], step, x + 4 * i);
     } else {
@@ -362,14 +400,14 @@ __device__ __forceinline__ void load_payload(const void *pay, uint64_t e0, uint3
         for (int i = 0; i < G::kQuads; ++i)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const uint32_t idx = 4 * (i * G::kThreads + threadIdx.x) + e;
+                const uint32_t idx = 4 * G::quad(i) + e;
                 r[4 * i + e] = C::decode1(pay, e0 + min(idx, len - 1), step);
             }
 #pragma unroll
         for (int i = 0; i < G::kQuads; ++i)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const uint32_t idx = 4 * (i * G::kThreads + threadIdx.x) + e;
+                const uint32_t idx = 4 * G::quad(i) + e;
                 x[4 * i + e] = idx < len ? r[4 * i + e] : 0.0f;
             }
     }
@@ -397,14 +435,21 @@ __device__ __forceinline__ void store_payload(void *pay, float *sc, uint64_t e0,
     const float inv = MODE == PIPESGD_QUANT8 ? quant_inverse(scale) : 0.0f;
     if (FULL) {
         typename C::Raw *v = reinterpret_cast<typename C::Raw *>(static_cast<char *>(pay) + e0 * C::kBytes);
+        if constexpr (kWide128<C, G>) {
+            typename C::Raw r[G::kQuads];
 #pragma unroll
-        for (int i = 0; i < G::kQuads; ++i) st<NT>(v + i * G::kThreads + threadIdx.x, C::encode(x + 4 * i, inv));
+            for (int i = 0; i < G::kQuads; ++i) r[i] = C::encode(x + 4 * i, inv);
+            st<NT>(reinterpret_cast<u32x4 *>(v) + threadIdx.x, join128<C>(r));
+        } else {
+#pragma unroll
+            for (int i = 0; i < G::kQuads; ++i) st<NT>(v + G::quad(i), C::encode(x + 4 * i, inv));
+        }
     } else {
 #pragma unroll
         for (int i = 0; i < G::kQuads; ++i)
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const uint32_t idx = 4 * (i * G::kThreads + threadIdx.x) + e;
+                const uint32_t idx = 4 * G::quad(i) + e;
                 if (idx < len) C::encode1(pay, e0 + idx, x[4 * i + e], inv);
             }
     }

@@ -365,6 +365,57 @@ __global__ __launch_bounds__(G::kThreads) void update_kernel(UpdateArgs a)
     else        update_body<MODE, MOMENTUM, G, false>(a, t, r, scale);
 }
 
+// Measurement aid, not part of the method: the update's memory streams with the
+// arithmetic taken out, over the update's own buffers and grid.  Whole units only.
+//   kProbeRead : loads slot, w, v of a unit; stores nothing (the loads feed a test that never holds)
+//   kProbeWrite: stores a bit pattern derived from the index into w and v
+//   kProbeMixed: loads slot, w, v; stores v's values into w and w's into v -- the
+//                update's 10 bytes read : 8 written per element (TRUNC16), no FMAs
+//   kProbeCopy : loads w, stores it into v (the classic 1 : 1 copy)
+enum { kProbeRead = 0, kProbeWrite = 1, kProbeMixed = 2, kProbeCopy = 3 };
+
+template <int MODE, int KIND, class G>
+__global__ __launch_bounds__(G::kThreads) void stream_probe_kernel(UpdateArgs a, uint32_t salt)
+{
+    const int r = blockIdx.y;
+    const uint64_t e0 = static_cast<uint64_t>(blockIdx.x) * G::kUnit;
+    float *w = a.w[r] + e0;
+    float *v = a.v[r] + e0;
+    float g[G::kPerThread], wv[G::kPerThread], vv[G::kPerThread];
+    if (KIND == kProbeRead || KIND == kProbeMixed) {
+        load_payload<MODE, G, true, kNtUpdate>(a.pay[r], e0, G::kUnit, 1.0f, g);
+        load_f32<G, true, kNtUpdate>(w, G::kUnit, wv);
+        load_f32<G, true, kNtUpdate>(v, G::kUnit, vv);
+    } else if (KIND == kProbeCopy) {
+        load_f32<G, true, kNtUpdate>(w, G::kUnit, wv);
+    }
+    if (KIND == kProbeRead) {
+        uint32_t acc = 0;
+#pragma unroll
+        for (int k = 0; k < G::kPerThread; ++k) acc |= f2u(g[k]) ^ f2u(wv[k]) ^ f2u(vv[k]);
+        if (acc == salt) w[threadIdx.x] = u2f(salt);          // the compiler cannot rule it out, so every load stays;
+                                                              // in practice it never holds (and the probes' data is scratch)
+    } else if (KIND == kProbeWrite) {
+#pragma unroll
+        for (int k = 0; k < G::kPerThread; ++k) {
+            const uint32_t h = (static_cast<uint32_t>(e0) + threadIdx.x * G::kPerThread + k) * 2654435761u + salt;
+            wv[k] = u2f(0x3a000000u | (h >> 9));               // finite, varied mantissas, magnitudes near 5e-4
+            vv[k] = u2f(0xba000000u | (h & 0x007fffffu));
+        }
+        store_f32<G, true, kNtUpdate>(v, G::kUnit, vv);
+        store_f32<G, true, kNtUpdate>(w, G::kUnit, wv);
+    } else if (KIND == kProbeMixed) {
+        uint32_t acc = 0;
+#pragma unroll
+        for (int k = 0; k < G::kPerThread; ++k) acc |= f2u(g[k]);
+        if (acc == salt) vv[0] = u2f(salt);                   // as above: keeps every payload load alive
+        store_f32<G, true, kNtUpdate>(v, G::kUnit, wv);
+        store_f32<G, true, kNtUpdate>(w, G::kUnit, vv);
+    } else {
+        store_f32<G, true, kNtUpdate>(v, G::kUnit, wv);
+    }
+}
+
 // A whole width-2 iteration in ONE launch, for gradients so small that launch
 // latency, not bandwidth, sets the pace: the AllReduce of this iteration's
 // gradients (chain in registers, as in ring_fused_kernel) and the update from
@@ -732,6 +783,24 @@ int launch_update(const LaunchConfig &c, const UpdateArgs &ua, int replicas, hip
         if (units > 0x7fffffffull) return PIPESGD_ERR_CAPACITY;                                                  \
         return launch(update_kernel<MODE, MOMENTUM, G>, dim3(static_cast<uint32_t>(units), replicas), T,         \
                       c.lds_bytes, s, done, ua);                                                                 \
+    }
+    PIPESGD_FOR_EACH_GEO(X)
+#undef X
+    return PIPESGD_ERR_ARG;
+}
+
+template <int MODE, int KIND>
+int launch_probe(const LaunchConfig &c, const UpdateArgs &ua, int replicas, hipStream_t s)
+{
+#define X(T, Q)                                                                                                  \
+    if (c.threads == T && c.quads == Q) {                                                                        \
+        static std::atomic<uint32_t> done{0};                                                                    \
+        using G = Geo<T, Q>;                                                                                     \
+        const uint64_t units = ua.n / G::kUnit;                                                                  \
+        if (units > 0x7fffffffull) return PIPESGD_ERR_CAPACITY;                                                  \
+        if (units == 0) return PIPESGD_OK;                                                                       \
+        return launch(stream_probe_kernel<MODE, KIND, G>, dim3(static_cast<uint32_t>(units), replicas), T,       \
+                      c.lds_bytes, s, done, ua, 0x9e3779b9u);                                                    \
     }
     PIPESGD_FOR_EACH_GEO(X)
 #undef X
@@ -1280,6 +1349,33 @@ int pipesgd_apply_update_multi(int mode, int replicas, const void *const *g_sum_
     const LaunchConfig c = cfg_of(kUpdate, mode);
     hipStream_t s = static_cast<hipStream_t>(stream);
 #define CALL(M) return mom ? launch_update<M, true>(c, ua, replicas, s) : launch_update<M, false>(c, ua, replicas, s);
+    PIPESGD_MODE_SWITCH(mode, CALL)
+#undef CALL
+    return PIPESGD_ERR_MODE;
+}
+
+int pipesgd_probe_stream(int kind, int mode, int replicas, const void *const *g_sum_c, float *const *w, float *const *v,
+                         uint64_t n, int threads, int quads, int lds_bytes, void *stream)
+{
+    if (kind < kProbeRead || kind > kProbeCopy) return PIPESGD_ERR_ARG;
+    if (mode != PIPESGD_TRUNC16 && mode != PIPESGD_QUANT8 && mode != PIPESGD_NONE) return PIPESGD_ERR_MODE;
+    const LaunchConfig c = {threads, quads, lds_bytes};
+    if (!config_ok(kUpdate, mode, c)) return PIPESGD_ERR_ARG;
+    UpdateArgs ua;
+    // the same checks as the update's (momentum form: v is needed); the probes never read scales
+    alignas(16) static const float no_scale[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    const float *sc[kMaxW];
+    for (int r = 0; r < kMaxW; ++r) sc[r] = no_scale;
+    const int rc = prepare_update(mode, replicas, g_sum_c, sc, n, w, v, 0.0f, 0.5f, 1.0f, ua);
+    if (rc != PIPESGD_OK) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+#define CALL(M)                                                                            \
+    switch (kind) {                                                                        \
+    case kProbeRead:  return launch_probe<M, kProbeRead>(c, ua, replicas, s);              \
+    case kProbeWrite: return launch_probe<M, kProbeWrite>(c, ua, replicas, s);             \
+    case kProbeMixed: return launch_probe<M, kProbeMixed>(c, ua, replicas, s);             \
+    default:          return launch_probe<M, kProbeCopy>(c, ua, replicas, s);              \
+    }
     PIPESGD_MODE_SWITCH(mode, CALL)
 #undef CALL
     return PIPESGD_ERR_MODE;

@@ -7,6 +7,7 @@
 
 #include <cstdint>
 #include <new>
+#include <vector>
 
 #include "pipesgd.h"
 #include "pipesgd_internal.hpp"
@@ -40,6 +41,10 @@ struct pipesgd_runtime {
     hipEvent_t sum_ready[kEventRing];     // g_sum[t] is ready     (comm -> compute)
     uint64_t t = 0;                    // iterations enqueued so far
     bool ok = false;
+    // PIPESGD_RT_TIME_UPDATE: one (start, stop) pair of timing events per timed update launch,
+    // reused after pipesgd_runtime_update_time has read them
+    std::vector<hipEvent_t> timing;
+    size_t timed = 0;                  // pairs recorded since the last read-out
 };
 
 extern "C" {
@@ -70,6 +75,7 @@ void pipesgd_runtime_destroy(pipesgd_runtime *rt)
         if (rt->local_ready[i]) (void)hipEventDestroy(rt->local_ready[i]);
         if (rt->sum_ready[i]) (void)hipEventDestroy(rt->sum_ready[i]);
     }
+    for (hipEvent_t e : rt->timing) (void)hipEventDestroy(e);
     if (rt->compute) (void)hipStreamDestroy(rt->compute);
     if (rt->comm) (void)hipStreamDestroy(rt->comm);
     delete rt;
@@ -89,6 +95,22 @@ int pipesgd_runtime_sync(pipesgd_runtime *rt)
     return PIPESGD_OK;
 }
 
+int pipesgd_runtime_update_time(pipesgd_runtime *rt, double *total_ms, uint64_t *launches)
+{
+    if (!rt || !rt->ok || !total_ms || !launches) return PIPESGD_ERR_ARG;
+    if (hipStreamSynchronize(rt->compute) != hipSuccess) return PIPESGD_ERR_HIP;
+    double sum = 0.0;
+    for (size_t i = 0; i < rt->timed; ++i) {
+        float ms = 0.0f;
+        if (hipEventElapsedTime(&ms, rt->timing[2 * i], rt->timing[2 * i + 1]) != hipSuccess) return PIPESGD_ERR_HIP;
+        sum += static_cast<double>(ms);
+    }
+    *total_ms = sum;
+    *launches = rt->timed;
+    rt->timed = 0;
+    return PIPESGD_OK;
+}
+
 int pipesgd_synthetic_compute(float duration_us, int workgroups, void *stream)
 {
     const int rc = pipesgd_internal_check_standin(duration_us, workgroups);
@@ -103,7 +125,7 @@ int pipesgd_synthetic_compute(float duration_us, int workgroups, void *stream)
 int pipesgd_runtime_iteration(pipesgd_runtime *rt, const pipesgd_runtime_iter *it)
 {
     if (!rt || !rt->ok || !it || !it->ring) return PIPESGD_ERR_ARG;
-    if (it->width < 1 || it->width >= kEventRing || it->reserved != 0) return PIPESGD_ERR_ARG;
+    if (it->width < 1 || it->width >= kEventRing || (it->flags & ~PIPESGD_RT_TIME_UPDATE) != 0) return PIPESGD_ERR_ARG;
     const int wg = it->compute_workgroups > 0 ? it->compute_workgroups : 1;
     // Everything is checked here, before the first launch or event record: a rejected call leaves both
     // streams, the events and the iteration count as they were, and the same iteration can be issued again.
@@ -117,6 +139,32 @@ int pipesgd_runtime_iteration(pipesgd_runtime *rt, const pipesgd_runtime_iter *i
     if (rc == PIPESGD_OK) rc = pipesgd_internal_check_standin(it->compute_us, wg);
     if (rc == PIPESGD_OK) rc = pipesgd_internal_check_standin(it->wire_us, 1);
     if (rc != PIPESGD_OK) return rc;
+    hipEvent_t t_start = nullptr, t_stop = nullptr;     // host objects only; made before anything is enqueued
+    if (it->flags & PIPESGD_RT_TIME_UPDATE) {
+        try {
+            while (rt->timing.size() < 2 * (rt->timed + 1)) {
+                hipEvent_t e;
+                if (hipEventCreate(&e) != hipSuccess) return PIPESGD_ERR_HIP;
+                rt->timing.push_back(e);
+            }
+        } catch (const std::bad_alloc &) {
+            return PIPESGD_ERR_CAPACITY;
+        }
+        t_start = rt->timing[2 * rt->timed];
+        t_stop = rt->timing[2 * rt->timed + 1];
+    }
+    // the update launch, bracketed by the timing events when asked for
+    auto update = [&](const void *const *g_sum_c, const float *const *scales) -> int {
+        if (t_start && hipEventRecord(t_start, rt->compute) != hipSuccess) return PIPESGD_ERR_HIP;
+        const int urc = pipesgd_apply_update_multi(it->ring->mode, it->replicas, g_sum_c, scales, it->ring->n, it->w, it->v,
+                                                   it->lr, it->momentum, it->grad_scale, rt->compute);
+        if (urc != PIPESGD_OK) return urc;
+        if (t_stop) {
+            if (hipEventRecord(t_stop, rt->compute) != hipSuccess) return PIPESGD_ERR_HIP;
+            ++rt->timed;
+        }
+        return PIPESGD_OK;
+    };
 
     const uint64_t t = rt->t + 1;                       // this call is iteration t (1-based)
     hipEvent_t sum_ready = rt->sum_ready[t % kEventRing];
@@ -137,8 +185,7 @@ int pipesgd_runtime_iteration(pipesgd_runtime *rt, const pipesgd_runtime_iter *i
         // stand-in for batch/forward/backward that yields g[t+1], and mark it ready
         if (t > lag && hipStreamWaitEvent(rt->compute, rt->sum_ready[(t - lag) % kEventRing], 0) != hipSuccess)
             return PIPESGD_ERR_HIP;
-        rc = pipesgd_apply_update_multi(it->ring->mode, it->replicas, it->stale_g_sum_c, it->stale_scales, it->ring->n,
-                                        it->w, it->v, it->lr, it->momentum, it->grad_scale, rt->compute);
+        rc = update(it->stale_g_sum_c, it->stale_scales);
         if (rc != PIPESGD_OK) return rc;
         rc = pipesgd_synthetic_compute(it->compute_us, wg, rt->compute);
         if (rc != PIPESGD_OK) return rc;
@@ -156,8 +203,7 @@ int pipesgd_runtime_iteration(pipesgd_runtime *rt, const pipesgd_runtime_iter *i
         if (rc != PIPESGD_OK) return rc;
         if (hipEventRecord(sum_ready, rt->comm) != hipSuccess) return PIPESGD_ERR_HIP;
         if (hipStreamWaitEvent(rt->compute, sum_ready, 0) != hipSuccess) return PIPESGD_ERR_HIP;
-        rc = pipesgd_apply_update_multi(it->ring->mode, it->replicas, it->fresh_g_sum_c, it->fresh_scales, it->ring->n,
-                                        it->w, it->v, it->lr, it->momentum, it->grad_scale, rt->compute);
+        rc = update(it->fresh_g_sum_c, it->fresh_scales);
         if (rc != PIPESGD_OK) return rc;
     }
     rt->t = t;

@@ -603,8 +603,11 @@ def test_two_stream_runtime_matches_oracle(orc, mode, width):
         sync()
         cur = t % K
         rt.iteration(sim.rings[cur], sim.updates[(cur + 1) % K], sim.updates[cur], B.STEPWISE, width, lr, m, 1.0,
-                     compute_us=150.0, compute_workgroups=8)
+                     compute_us=150.0, compute_workgroups=8, time_update=(t % 2 == 1))
     rt.sync()
+    total_ms, timed = rt.update_time()                   # every other update launch was bracketed by timing events
+    assert timed == (iters + 1) // 2 and 0.0 < total_ms < 50.0 * timed
+    assert rt.update_time() == (0.0, 0)                  # read out and started anew
     ws, vs = orc.pipe_sgd_run(mode, grad_fn, w0, p, iters, lr, m, 1.0, width)
     for r in range(p):
         assert_fp32_close_then_exact(sim.model(r), ws[r], f"w r={r}")
@@ -669,7 +672,7 @@ def test_runtime_rejected_call_enqueues_nothing_and_the_runtime_goes_on(orc, wid
         it = B.RuntimeIter()
         it.ring = C.pointer(ring)
         it.schedule, it.width, it.replicas, it.compute_workgroups = B.STEPWISE, width, p, 2
-        it.compute_us, it.wire_us, it.lr, it.momentum, it.grad_scale, it.reserved = 20.0, 10.0, lr, m, 1.0, 0
+        it.compute_us, it.wire_us, it.lr, it.momentum, it.grad_scale, it.flags = 20.0, 10.0, lr, m, 1.0, 0
         it.stale_g_sum_c = C.cast(stale.g_sum_c, C.c_void_p)
         it.fresh_g_sum_c = C.cast(fresh.g_sum_c, C.c_void_p)
         it.w, it.v = C.cast(stale.w, C.c_void_p), C.cast(stale.v, C.c_void_p)
@@ -689,7 +692,7 @@ def test_runtime_rejected_call_enqueues_nothing_and_the_runtime_goes_on(orc, wid
         (lambda it: setattr(it, "wire_us", float("nan")), -1),
         (lambda it: setattr(it, "compute_workgroups", 70000), -1),
         (lambda it: setattr(it, "schedule", 7), -3),
-        (lambda it: setattr(it, "reserved", 1), -1),
+        (lambda it: setattr(it, "flags", 2), -1),
     ]
     for t in range(1, iters + 1):
         rt.sync()
