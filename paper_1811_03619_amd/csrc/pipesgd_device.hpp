@@ -27,8 +27,10 @@ constexpr int kMaxB = PIPESGD_MAX_BUCKETS;
 // run.  Lane-contiguous (build with -DPIPESGD_LANE_CONTIGUOUS=1): quad i of thread t
 // is quad t*QUADS + i, so a thread's 16-bit (QUADS = 2) or 8-bit (QUADS = 4) payload
 // is ONE 128-bit load, at the price of fp32 loads whose lanes sit 32 or 64 bytes
-// apart.  Measured slower on MI355X, so it is off; kept as a build option because
-// results do not depend on it (the parity tests pass with either).
+// apart.  Measured slower on MI355X (16-bit update at 61M elements: 5.8 TB/s with
+// QUADS = 2 and 3.4 TB/s with QUADS = 4, against 6.5 TB/s strided; the hop kernels
+// lose 4-11 %), so it is off; kept as a build option because results do not depend
+// on it (the parity tests pass with either).
 #ifndef PIPESGD_LANE_CONTIGUOUS
 #define PIPESGD_LANE_CONTIGUOUS 0
 #endif

@@ -1,6 +1,8 @@
 """GPU parity at the full sizes of the workload list, in the launch
-configuration bench.py times (p = 4, stepwise schedule, all replicas updated in
-one launch, width 2).  The scalar oracle finishes one full-size iteration in a
+configurations bench.py times (p = 4, all replicas updated in one launch, width
+2; stepwise schedule on one stream, and for the bucketed workload through the
+two-stream runtime, which is what bench.py runs it on by default), plus every
+other schedule bench.py can quote a figure for.  The scalar oracle finishes one full-size iteration in a
 second or two, so every output element is compared, not a sample.
 """
 import time
@@ -52,19 +54,25 @@ def oracle_allreduce(orc, schedule, mode, grads, buckets):
     return out
 
 
-@pytest.mark.parametrize("cfg,mode,schedule", [
-    (3, B.TRUNC16, B.STEPWISE),     # the headline configuration
-    (3, B.TRUNC16, B.FUSED),
-    (4, B.QUANT8, B.STEPWISE),
-    (5, B.NONE, B.STEPWISE),
-    (5, B.TRUNC16, B.STEPWISE),
-    (5, B.TRUNC16, B.FUSED),
-    (3, B.TRUNC16, B.DIRECT),       # the other schedules, each against its own oracle branch
-    (3, B.TRUNC16, B.HALVING_DOUBLING),
-    (5, B.TRUNC16, B.HALVING_DOUBLING),
-    (4, B.QUANT8, B.DIRECT),
+@pytest.mark.parametrize("cfg,mode,schedule,streams", [
+    (3, B.TRUNC16, B.STEPWISE, 1),     # the headline configuration
+    (3, B.TRUNC16, B.FUSED, 1),
+    (4, B.QUANT8, B.STEPWISE, 1),
+    (4, B.QUANT8, B.FUSED, 1),
+    (5, B.NONE, B.STEPWISE, 1),
+    (5, B.NONE, B.FUSED, 1),
+    (5, B.TRUNC16, B.STEPWISE, 1),
+    (5, B.TRUNC16, B.STEPWISE, 2),     # bench.py's default for the bucketed workload: the two-stream runtime
+    (5, B.NONE, B.STEPWISE, 2),
+    (5, B.TRUNC16, B.FUSED, 1),
+    (5, B.TRUNC16, B.ONE_LAUNCH, 1),   # AllReduce and update of an iteration in one launch
+    (3, B.TRUNC16, B.DIRECT, 1),       # the other schedules, each against its own oracle branch
+    (3, B.TRUNC16, B.HALVING_DOUBLING, 1),
+    (5, B.TRUNC16, B.HALVING_DOUBLING, 1),
+    (5, B.TRUNC16, B.DIRECT, 1),
+    (4, B.QUANT8, B.DIRECT, 1),
 ])
-def test_full_size_two_iterations(orc, cfg, mode, schedule):
+def test_full_size_two_iterations(orc, cfg, mode, schedule, streams):
     p, lr, m = 4, 0.01, 0.9
     t0 = time.time()
     buckets, n, grads = full_config_inputs(cfg, p, seed=1)
@@ -74,8 +82,19 @@ def test_full_size_two_iterations(orc, cfg, mode, schedule):
     sim = PipeSgdSim(mode, p, n, lr, m, 1.0, 2, buckets, schedule)
     sim.set_gradients(grads)
     sim.set_model(w0)
-    sim.iteration()            # t=1: AllReduce -> slot 1, update from the zero slot
-    sim.iteration()            # t=2: AllReduce -> slot 0, update from slot 1
+    if streams == 1:
+        sim.iteration()        # t=1: AllReduce -> slot 1, update from the zero slot
+        sim.iteration()        # t=2: AllReduce -> slot 0, update from slot 1
+    else:
+        sync()
+        rt = B.Runtime()
+        for t in (1, 2):       # the same two iterations, AllReduce on one stream and update on the other
+            cur = t % 2
+            rt.iteration(sim.rings[cur], sim.updates[1 - cur], sim.updates[cur], schedule, 2, lr, m, 1.0,
+                         time_update=True)
+        rt.sync()
+        assert rt.update_time()[1] == 2
+        rt.close()
     sync()
 
     t0 = time.time()

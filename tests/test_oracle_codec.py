@@ -124,6 +124,26 @@ def test_quant8_blocks_are_independent_4096_runs(orc):
     assert y[8192] == -3.0 and y[4096] == 0.25 and y[0] == 1.0
 
 
+def test_quant8_operation_order_against_the_workload_formula(orc):
+    # The workload list writes the code as round(x / scale * 127); the reading taken here is
+    # rint(x * (127 / scale)) -- one division per block instead of one per element.  In binary32 the two
+    # differ only where x/scale*127 falls within an ulp or so of a rounding tie: about one element in a
+    # million on Gaussian blocks, and then by exactly one code.  The oracle must follow the reading taken
+    # (bit for bit, against numpy's correctly rounded float32 operations), and the literal formula must
+    # stay that close to it -- which is all that can be pinned: no text fixes the order of operations.
+    x = W.gaussian(4096 * 1500, 1e-4, 71)
+    pay, sc = orc.compress(orc.QUANT8, x)
+    xb = x.reshape(-1, 4096)
+    s = np.abs(xb).max(axis=1, keepdims=True).astype(np.float32)
+    assert np.array_equal(sc, s.ravel())
+    taken = np.clip(np.rint(xb * (np.float32(127.0) / s)), -127, 127).astype(np.int8)
+    literal = np.clip(np.rint((xb / s) * np.float32(127.0)), -127, 127).astype(np.int8)
+    assert np.array_equal(pay.reshape(-1, 4096), taken)
+    differ = taken != literal
+    assert differ.mean() < 1e-5
+    assert np.abs(taken.astype(np.int16) - literal.astype(np.int16)).max() <= 1
+
+
 def test_quant8_zero_block(orc):
     x = np.zeros(4096 + 7, dtype=np.float32)
     x[4096 + 3] = 1e-3
