@@ -336,7 +336,7 @@ def main() -> int:
     if args.phases:
         out["phases_ms"] = time_phases(sim, B, torch, np)
     if buckets:
-        out["bucketing"] = time_packing(sim, B, torch, np, numels, offs, n, model["total"])
+        out["bucketing"] = time_packing(sim, B, torch, np, numels, offs, n, model["total"], with_iteration=args.phases)
     if args.phases:
         out["ceiling"] = stream_ceiling(sim, B, torch, np)         # last: the probes overwrite w and v
 
@@ -370,12 +370,12 @@ def main() -> int:
     return 0
 
 
-def time_packing(sim, B, torch, np, numels, offs, n, iter_bytes, reps: int = 20):
+def time_packing(sim, B, torch, np, numels, offs, n, iter_bytes, with_iteration: bool, reps: int = 20):
     """Step a0, timed on its own (it is NOT part of the timed iteration, whose
     gradients already sit in the packed buffers): gather every worker's
     per-layer gradient tensors into its packed buffer, one launch for all
-    tensors of all workers, and the scatter back.  Also the iteration with one
-    gather launch put in front of every AllReduce."""
+    tensors of all workers, and the scatter back.  With --phases also the
+    iteration with one gather launch put in front of every AllReduce."""
     p, dev = sim.p, sim.device
     starts = np.cumsum([0] + [ne + (-ne) % 4 for ne in numels])        # 16-byte aligned tensors in one arena
     arenas = [torch.randn(int(starts[-1]), device=dev) * 1e-3 for _ in range(p)]
@@ -409,7 +409,7 @@ def time_packing(sim, B, torch, np, numels, offs, n, iter_bytes, reps: int = 20)
     res = {"tensors": len(numels), "workers": p, "launches": 1, "pack_ms": round(pack_ms, 5),
            "unpack_ms": round(unpack_ms, 5), "pack_GBps": round(moved / pack_ms / 1e6, 1),
            "unpack_GBps": round(moved / unpack_ms / 1e6, 1), "included_in_value": False}
-    if sim.schedule in (B.STEPWISE, B.FUSED):
+    if with_iteration and sim.schedule in (B.STEPWISE, B.FUSED):
         rt = B.Runtime()
         comm = rt.stream(1)
 
