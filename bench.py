@@ -7,6 +7,12 @@ workers (first send, p-1 transmit-and-reduce rounds with decompress-sum-
 compress, p-1 send-back rounds, every hop's payload written to memory) and the
 staleness-1 momentum-SGD update of all p model replicas.
 
+The iterations run the way Algorithm 1 runs them: the AllReduce on the
+communication stream, the update on the computation stream (the library's
+two-stream runtime), so the AllReduce of iteration t overlaps the update that
+applies iteration t-1's result.  One further block of iterations runs on one
+stream so that the update kernel, the dominant one, is also timed alone.
+
 Prints ONE JSON line.  `value` is algorithmic GB/s: the bytes the method moves
 per iteration (every hop's payload written once and read once, every replica's
 slot/w/v read and w/v written once) divided by the measured time.
@@ -100,9 +106,12 @@ def main() -> int:
                     help="replay the iterations from a captured HIP graph (two iterations per replay); "
                          "the update kernel is then not bracketed by events, so roofline.achieved is null")
     ap.add_argument("--streams", choices=["auto", "1", "2"], default="auto",
-                    help="1: AllReduce and update back to back on one stream.  2: through the library's two-stream "
-                         "runtime (Algorithm 1's two threads: the AllReduce on one stream, the update on the other).  "
-                         "auto: 2 for bucketed workloads (many short launches, which the update then hides), else 1")
+                    help="2: through the library's two-stream runtime (Algorithm 1's two threads: the AllReduce on the "
+                         "communication stream, the update on the computation stream, ordered by events), which is how "
+                         "the method runs; one more block of --steps iterations then runs on one stream to time the "
+                         "update kernel alone.  1: AllReduce and update back to back on one stream.  auto: 2 for the "
+                         "ring schedules (stepwise, fused) on vectors of 4M elements or more, 1 for launch-bound "
+                         "sizes, the other schedules and --graph")
     ap.add_argument("--two-streams", action="store_true", help="same as --streams 2")
     ap.add_argument("--no-stagger", action="store_true",
                     help="place every buffer at the start of a 4 KiB page instead of staggering them by multiples of "
@@ -152,7 +161,9 @@ def main() -> int:
     if args.two_streams:
         streams = "2"
     if streams == "auto":
-        streams = "2" if (buckets and schedule in (B.STEPWISE, B.FUSED) and not args.graph) else "1"
+        # launch-bound sizes (configs 1 and 2: a few MB per worker) lose on two streams: the event hand-offs
+        # cost more than the overlap gains
+        streams = "2" if (schedule in (B.STEPWISE, B.FUSED) and not args.graph and n >= (1 << 22)) else "1"
     two_streams = streams == "2"
 
     def host_gradient(r: int) -> np.ndarray:
@@ -226,23 +237,27 @@ def main() -> int:
             for _ in range(k):
                 sim.iteration()
 
-        def run_block(k):
-            ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(k)]
-            torch.cuda.synchronize()
-            t_begin = time.perf_counter()
-            if schedule == B.ONE_LAUNCH:
-                for _ in range(k):
-                    sim.iteration()
-            else:
-                for i in range(k):
-                    cur = sim.allreduce()
-                    ev[i][0].record()
-                    sim.update_from(1 - cur)
-                    ev[i][1].record()
-                    sim.t += 1
-            torch.cuda.synchronize()
-            wall = time.perf_counter() - t_begin
-            return wall, ([a.elapsed_time(b) for a, b in ev] if schedule != B.ONE_LAUNCH else [])
+    def run_block_one_stream(k):
+        """k iterations back to back on torch's current stream, every update launch bracketed by events on it."""
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(k)]
+        torch.cuda.synchronize()
+        t_begin = time.perf_counter()
+        if schedule == B.ONE_LAUNCH:
+            for _ in range(k):
+                sim.iteration()
+        else:
+            for i in range(k):
+                cur = sim.allreduce()
+                ev[i][0].record()
+                sim.update_from(1 - cur)
+                ev[i][1].record()
+                sim.t += 1
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t_begin
+        return wall, ([a.elapsed_time(b) for a, b in ev] if schedule != B.ONE_LAUNCH else [])
+
+    if not two_streams and not args.graph:
+        run_block = run_block_one_stream
 
     block(args.warmup, timed=False)
     (rt.sync() if rt else torch.cuda.synchronize())
@@ -258,7 +273,17 @@ def main() -> int:
         upd_all += upd
     ms_per_step = float(np.median(block_ms))
     upd_ms = float(np.mean(upd_all)) if upd_all else None
+    alone = None
     if rt is not None:
+        # Beside the AllReduce launches of the other stream the update shares the memory bandwidth, so its
+        # duration there says nothing about the kernel.  One more block of `steps` iterations, on one stream,
+        # times it alone (the roofline figure); that block does not enter ms_per_step.
+        rt.sync()
+        for _ in range(2):
+            sim.iteration()
+        wall_s, upd_alone = run_block_one_stream(args.steps)
+        alone = {"ms_per_step": wall_s * 1e3 / args.steps, "launch_ms": float(np.mean(upd_alone)), "launches": len(upd_alone)}
+        overlapped_ms, upd_ms, upd_all = upd_ms, alone["launch_ms"], upd_alone
         rt.close()
 
     n_true = int(sum(numels))          # bucket padding is processed but is not part of the model
@@ -322,16 +347,24 @@ def main() -> int:
             "traffic_note": traffic_note,
             "launch_ms": round(upd_ms, 5) if upd_ms else None, "launches_timed": len(upd_all),
             "algorithmic_bytes_per_launch": int(model["update"]),
-            "overlapped": bool(two_streams),
             "launch_geometry": dict(zip(("threads", "quads", "lds_bytes"), B.get_launch_config(B.K_UPDATE, mode))),
         },
         "kernel_sources_sha256": kernel_sources_sha256(),
         "input_generation_s": round(gen_s, 2),
     }
-    if two_streams:
-        out["roofline"]["note"] = ("the update runs beside the AllReduce launches of the other stream and shares the "
-                                   "memory bandwidth with them, so its own duration is longer than alone "
-                                   "(--streams 1 times it alone)")
+    if alone is not None:
+        out["roofline"]["measured_in"] = (
+            f"one more block of {args.steps} iterations run back to back on one stream after the {args.repeats} "
+            f"two-stream blocks, where the kernel has the memory to itself (that block: "
+            f"{round(alone['ms_per_step'], 5)} ms per iteration; `bench.py --streams 1` runs everything that way)")
+        out["roofline"]["beside_the_allreduce"] = {
+            "launch_ms": round(overlapped_ms, 5) if overlapped_ms else None,
+            "note": "duration of the same launch in the two-stream blocks, where the AllReduce kernels of the other "
+                    "stream run beside it and share the bandwidth: not a figure of the kernel",
+        }
+        out["one_stream_ms_per_step"] = round(alone["ms_per_step"], 5)
+    else:
+        out["roofline"]["measured_in"] = "every timed iteration (one stream: the kernel runs alone)"
 
     if args.phases:
         out["phases_ms"] = time_phases(sim, B, torch, np)
