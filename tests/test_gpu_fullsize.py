@@ -55,14 +55,16 @@ def oracle_allreduce(orc, schedule, mode, grads, buckets):
 
 
 @pytest.mark.parametrize("cfg,mode,schedule,streams", [
-    (3, B.TRUNC16, B.STEPWISE, 1),     # the headline configuration
+    (3, B.TRUNC16, B.STEPWISE, 2),     # the headline configuration as bench.py times it: the two-stream runtime
+    (3, B.TRUNC16, B.STEPWISE, 1),     # and back to back on one stream
     (3, B.TRUNC16, B.FUSED, 1),
+    (4, B.QUANT8, B.STEPWISE, 2),
     (4, B.QUANT8, B.STEPWISE, 1),
     (4, B.QUANT8, B.FUSED, 1),
     (5, B.NONE, B.STEPWISE, 1),
     (5, B.NONE, B.FUSED, 1),
     (5, B.TRUNC16, B.STEPWISE, 1),
-    (5, B.TRUNC16, B.STEPWISE, 2),     # bench.py's default for the bucketed workload: the two-stream runtime
+    (5, B.TRUNC16, B.STEPWISE, 2),
     (5, B.NONE, B.STEPWISE, 2),
     (5, B.TRUNC16, B.FUSED, 1),
     (5, B.TRUNC16, B.ONE_LAUNCH, 1),   # AllReduce and update of an iteration in one launch
