@@ -738,6 +738,49 @@ def test_synthetic_compute_takes_about_the_requested_time():
         B.synthetic_compute(10.0, 0)
 
 
+# ------------------------------------------------------- measurement probes --
+
+@pytest.mark.parametrize("mode", MODES)
+def test_stream_probes_touch_exactly_what_they_say(mode):
+    # pipesgd_probe_stream is measurement code, but it writes the caller's buffers: whole units only, nothing
+    # past them, and exactly the documented data movement.
+    p, n = 3, 4096 * 5 + 1500                        # the ragged tail must be left alone by every kind
+    rng = np.random.Generator(np.random.Philox(key=77))
+    w_h = [rng.standard_normal(n).astype(np.float32) for _ in range(p)]
+    v_h = [rng.standard_normal(n).astype(np.float32) for _ in range(p)]
+    slots = [pay_buf(mode, n) for _ in range(p)]
+    for (t, q, lds) in [(64, 4, 53248), (256, 1, 0), (256, 4, 0), (1024, 1, 65536)]:
+        whole = n // (t * q * 4) * (t * q * 4)
+        for kind in (B.PROBE_READ, B.PROBE_COPY, B.PROBE_MIXED, B.PROBE_WRITE):
+            w = [up(x) for x in w_h]
+            v = [up(x) for x in v_h]
+            ua = B.UpdateArgs(slots, None, w, v)
+            B.probe_stream(kind, mode, ua, n, t, q, lds)
+            sync()
+            for r in range(p):
+                gw, gv = down(w[r]), down(v[r])
+                assert_bits_equal(gw[whole:], w_h[r][whole:], f"w tail kind {kind}")
+                assert_bits_equal(gv[whole:], v_h[r][whole:], f"v tail kind {kind}")
+                if kind == B.PROBE_READ:
+                    assert_bits_equal(gw, w_h[r], "the read probe must not write w")
+                    assert_bits_equal(gv, v_h[r], "the read probe must not write v")
+                elif kind == B.PROBE_COPY:
+                    assert_bits_equal(gw, w_h[r], "copy keeps w")
+                    assert_bits_equal(gv[:whole], w_h[r][:whole], "copy: v <- w")
+                elif kind == B.PROBE_MIXED:
+                    assert_bits_equal(gw[:whole], v_h[r][:whole], "mixed: w <- v")
+                    assert_bits_equal(gv[:whole], w_h[r][:whole], "mixed: v <- w")
+                else:
+                    assert np.isfinite(gw).all() and np.isfinite(gv).all()
+                    assert (np.abs(gw[:whole]) < 1e-2).all() and (gv[:whole] < 0).all()
+    ua = B.UpdateArgs(slots, None, [up(x) for x in w_h], [up(x) for x in v_h])
+    for bad in [dict(kind=9), dict(t=100), dict(q=3), dict(lds=-1), dict(mode=5)]:
+        a = dict(kind=B.PROBE_COPY, mode=mode, t=256, q=1, lds=0); a.update(bad)
+        with pytest.raises(B.PipeSgdError):
+            B.probe_stream(a["kind"], a["mode"], ua, n, a["t"], a["q"], a["lds"])
+    sync()
+
+
 # ---------------------------------------------------------------- HIP graph --
 
 @pytest.mark.parametrize("mode,bucketed", [(B.NONE, False), (B.TRUNC16, True), (B.QUANT8, False)])

@@ -68,3 +68,47 @@ def test_static_scratch_allreduce_with_buckets(orc):
     assert len(buckets) > 2
     run_both(orc, B.QUANT8, 4, N, seed=55, buckets=buckets)
     run_both(orc, B.TRUNC16, 4, N, seed=56, buckets=buckets)
+
+
+@pytest.mark.parametrize("mode", [B.TRUNC16, B.QUANT8])
+def test_static_scratch_allreduce_replays_from_a_hip_graph(orc, mode):
+    # the callers this entry point is for: code under graph capture cannot allocate.  The call is captured
+    # together with the update that consumes its result; every replay -- with eager work and synchronisation
+    # in between -- is checked against the oracle's width-1 run (AllReduce, then update with that result).
+    import torch
+    from gpu_util import assert_bits_equal, assert_fp32_close_then_exact, dev_zeros, down, pay_buf, sync, up
+    p, n, lr, m = 4, 4096 * 9 + 77, 0.01, 0.9
+    grads = [W.gaussian(n, 1e-3, 61, (mode, r, 0, 0)) for r in range(p)]
+    w0 = W.gaussian(n, 0.05, 62)
+    g_dev = [up(g) for g in grads]
+    slots = [pay_buf(mode, n) for _ in range(p)]
+    scs = [dev_zeros(B.num_scales(mode, n), fill=-1.0) for _ in range(p)]
+    w = [up(w0) for _ in range(p)]
+    v = [dev_zeros(n, fill=0.0) for _ in range(p)]
+    q8 = mode == B.QUANT8
+    ring = B.make_ring(mode, n, g_dev, slots, scs if q8 else None)
+    ua = B.UpdateArgs(slots, scs if q8 else None, w, v)
+    B.allreduce_direct_static(ring)                  # first call on the device, outside capture: looks the array up
+    sync()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        B.allreduce_direct_static(ring)
+        B.apply_update_multi(mode, ua, n, lr, m, 1.0)
+    sync()
+    want = orc.allreduce_direct(mode, grads)
+    w_ref, v_ref = w0.copy(), np.zeros(n, np.float32)
+    other = torch.zeros(1 << 18, device="cuda:0")
+    for rep in range(3):
+        for t in slots:                              # the replay must rewrite the result, not find it there
+            t.fill_(0x11)
+        graph.replay()
+        other.add_(1.0)
+        sync()
+        orc.sgd_update(mode, want[0][0], want[0][1], w_ref, v_ref, lr, m, 1.0)
+        for r in range(p):
+            assert_bits_equal(down(slots[r], mode), want[r][0], f"payload r={r} replay {rep}")
+            assert_fp32_close_then_exact(down(w[r]), w_ref, f"w r={r} replay {rep}")
+            assert_fp32_close_then_exact(down(v[r]), v_ref, f"v r={r} replay {rep}")
+    assert float(other[0]) == 3.0
+
