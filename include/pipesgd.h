@@ -448,7 +448,9 @@ int   pipesgd_runtime_sync(pipesgd_runtime *rt);          /* host waits for both
  * HIP events on the compute stream) and the number of the update launches that
  * were timed (PIPESGD_RT_TIME_UPDATE) since the previous call, and starts anew.
  * While the AllReduce runs beside it on the other stream an update takes longer
- * than alone: both draw on the same memory bandwidth. */
+ * than alone: both draw on the same memory bandwidth.  At most 65536 timed
+ * launches are kept between two read-outs; a further timed iteration is refused
+ * with PIPESGD_ERR_CAPACITY (nothing enqueued). */
 int   pipesgd_runtime_update_time(pipesgd_runtime *rt, double *total_ms, uint64_t *launches);
 void *pipesgd_runtime_stream(pipesgd_runtime *rt, int which);   /* 0 = compute, 1 = comm: a hipStream_t */
 

@@ -31,6 +31,7 @@ __global__ __launch_bounds__(64) void synthetic_compute_kernel(uint64_t ticks, u
 }
 
 constexpr int kEventRing = 8;
+constexpr size_t kMaxTimed = 1u << 16;     // timed update launches kept until they are read out
 
 }  // namespace
 
@@ -141,6 +142,7 @@ int pipesgd_runtime_iteration(pipesgd_runtime *rt, const pipesgd_runtime_iter *i
     if (rc != PIPESGD_OK) return rc;
     hipEvent_t t_start = nullptr, t_stop = nullptr;     // host objects only; made before anything is enqueued
     if (it->flags & PIPESGD_RT_TIME_UPDATE) {
+        if (rt->timed >= kMaxTimed) return PIPESGD_ERR_CAPACITY;       // read the times out first
         try {
             while (rt->timing.size() < 2 * (rt->timed + 1)) {
                 hipEvent_t e;
