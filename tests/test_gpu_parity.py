@@ -494,6 +494,65 @@ def test_every_launch_geometry_gives_the_same_bits(orc, restore_launch_configs, 
     assert_fp32_close_then_exact(down(v), v0, "v")
 
 
+def test_two_host_threads_launch_while_a_third_retunes(orc, restore_launch_configs):
+    # The library keeps one piece of shared state, the launch-geometry table, one atomic word per entry: two
+    # host threads driving independent rings on their own streams while a third thread keeps changing
+    # geometries must each get the oracle's bits (results never depend on the geometry, and no launch may see
+    # half of an old and half of a new entry).
+    import threading
+    mode, p, n, iters = B.TRUNC16, 4, 4096 * 23 + 321, 25
+    jobs = []
+    for j in range(2):
+        grads = [W.gaussian(n, 1e-3, 90 + j, (j, r, 0, 0)) for r in range(p)]
+        g_dev, slots, scs = ring_buffers(mode, grads)
+        w0 = W.gaussian(n, 0.05, 95 + j)
+        w, v = [up(w0) for _ in range(p)], [dev_zeros(n, fill=0.0) for _ in range(p)]
+        jobs.append(dict(grads=grads, ring=B.make_ring(mode, n, g_dev, slots, None), slots=slots, w0=w0, w=w, v=v,
+                         ua=B.UpdateArgs(slots, None, w, v), stream=torch.cuda.Stream(), keep=g_dev))
+    sync()
+    stop, errors = threading.Event(), []
+
+    def retune():
+        geos = [(64, 4), (128, 2), (128, 4), (256, 1), (256, 2), (256, 4), (512, 1), (512, 2), (1024, 1)]
+        i = 0
+        while not stop.is_set():
+            t, q = geos[i % len(geos)]
+            for kind in (B.K_FIRST_SEND, B.K_REDUCE_SCATTER, B.K_UPDATE, B.K_ALLGATHER):
+                try:
+                    B.set_launch_config(kind, mode, t, q, (i % 3) * 32768)
+                except B.PipeSgdError:
+                    pass                                  # a geometry this kind does not take: table unchanged
+            i += 1
+
+    def drive(job):
+        try:
+            for _ in range(iters):
+                B.allreduce_sim(job["ring"], B.STEPWISE, job["stream"])
+                B.apply_update_multi(mode, job["ua"], n, 0.01, 0.9, 1.0, job["stream"])
+            job["stream"].synchronize()
+        except Exception as e:                            # pragma: no cover
+            errors.append(e)
+
+    threads = [threading.Thread(target=retune)] + [threading.Thread(target=drive, args=(job,)) for job in jobs]
+    for t in threads:
+        t.start()
+    for t in threads[1:]:
+        t.join()
+    stop.set()
+    threads[0].join()
+    sync()
+    assert not errors, errors
+    for job in jobs:
+        want = orc.allreduce(mode, job["grads"])
+        w_ref, v_ref = job["w0"].copy(), np.zeros(n, np.float32)
+        for _ in range(iters):
+            orc.sgd_update(mode, want[0][0], None, w_ref, v_ref, 0.01, 0.9, 1.0)
+        for r in range(p):
+            assert_bits_equal(down(job["slots"][r], mode), want[r][0], f"payload r={r}")
+            assert_fp32_close_then_exact(down(job["w"][r]), w_ref, f"w r={r}")
+            assert_fp32_close_then_exact(down(job["v"][r]), v_ref, f"v r={r}")
+
+
 def test_launch_config_validation():
     L = B.lib()
     assert L.pipesgd_set_launch_config(99, 0, 256, 4, 0) == -1
