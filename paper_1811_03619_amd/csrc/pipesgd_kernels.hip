@@ -1429,8 +1429,12 @@ static int segment_copy(const pipesgd_segment *segments, uint64_t num, uint64_t 
     if (num > 0x7fffffffull || total_tiles > 0x7fffffffull) return PIPESGD_ERR_CAPACITY;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const dim3 grid(static_cast<uint32_t>(total_tiles));
-    if (to_packed) hipLaunchKernelGGL((segment_copy_kernel<true>), grid, dim3(256), 0, s, segments, static_cast<uint32_t>(num));
-    else           hipLaunchKernelGGL((segment_copy_kernel<false>), grid, dim3(256), 0, s, segments, static_cast<uint32_t>(num));
+    // 36 KiB of (unused) LDS per workgroup admits four workgroups of one 16 KiB tile each per compute unit:
+    // as for the other streaming kernels, fewer requests in flight than full occupancy issues run faster
+    // (gather of 161 tensors x 4 workers, 818 MB moved: 5.5 TB/s against 5.1 TB/s without the cap)
+    constexpr int kPackLds = 36 * 1024;
+    if (to_packed) hipLaunchKernelGGL((segment_copy_kernel<true>), grid, dim3(256), kPackLds, s, segments, static_cast<uint32_t>(num));
+    else           hipLaunchKernelGGL((segment_copy_kernel<false>), grid, dim3(256), kPackLds, s, segments, static_cast<uint32_t>(num));
     return hipGetLastError() == hipSuccess ? PIPESGD_OK : PIPESGD_ERR_HIP;
 }
 
