@@ -499,6 +499,7 @@ double pipesgd_model_scaling_efficiency(double l_up, double l_comp, double l_com
 #define PIPESGD_K_UPDATE          4
 #define PIPESGD_K_COMPRESS        5
 #define PIPESGD_K_DECOMPRESS      6
+#define PIPESGD_K_DIRECT_REDUCE   7   /* owner-side kernel of pipesgd_allreduce_direct(_static) */
 int pipesgd_set_launch_config(int kernel, int mode, int threads, int quads, int lds_bytes);
 int pipesgd_get_launch_config(int kernel, int mode, int *threads, int *quads, int *lds_bytes);
 

@@ -39,7 +39,7 @@ EXPORTS = [
 ]
 PROBE_READ, PROBE_WRITE, PROBE_MIXED, PROBE_COPY = range(4)
 STATIC_SCRATCH_BYTES = 32 << 20
-K_FIRST_SEND, K_REDUCE_SCATTER, K_ALLGATHER, K_FUSED, K_UPDATE, K_COMPRESS, K_DECOMPRESS = range(7)
+K_FIRST_SEND, K_REDUCE_SCATTER, K_ALLGATHER, K_FUSED, K_UPDATE, K_COMPRESS, K_DECOMPRESS, K_DIRECT_REDUCE = range(8)
 
 
 class PipeSgdError(RuntimeError):

@@ -478,7 +478,7 @@ __global__ __launch_bounds__(256) void segment_copy_kernel(const pipesgd_segment
 
 // --------------------------------------------------------- launch configs --
 
-enum KernelKind { kFirstSend = 0, kReduceScatter, kAllGather, kFused, kUpdate, kCompress, kDecompress, kNumKinds };
+enum KernelKind { kFirstSend = 0, kReduceScatter, kAllGather, kFused, kUpdate, kCompress, kDecompress, kDirectReduce, kNumKinds };
 
 struct LaunchConfig {
     int threads, quads;
@@ -501,10 +501,11 @@ std::atomic<uint64_t> g_cfg[kNumKinds][3] = {
     /* first send     */ {pack_cfg(256, 4, 0), pack_cfg(128, 2, 0), pack_cfg(512, 2, 32768)},
     /* reduce-scatter */ {pack_cfg(128, 2, 0), pack_cfg(128, 2, 0), pack_cfg(256, 4, 32768)},
     /* all-gather     */ {pack_cfg(128, 2, 0), pack_cfg(256, 2, 0), pack_cfg(256, 1, 0)},
-    /* fused          */ {pack_cfg(256, 1, 0), pack_cfg(256, 1, 0), pack_cfg(256, 4, 0)},
+    /* fused          */ {pack_cfg(256, 1, 0), pack_cfg(512, 1, 49152), pack_cfg(256, 4, 61440)},
     /* update         */ {pack_cfg(256, 1, 65536), pack_cfg(64, 4, 53248), pack_cfg(64, 4, 53248)},
-    /* compress       */ {pack_cfg(256, 4, 0), pack_cfg(512, 2, 0), pack_cfg(512, 2, 0)},
-    /* decompress     */ {pack_cfg(256, 4, 0), pack_cfg(256, 2, 0), pack_cfg(128, 2, 0)},
+    /* compress       */ {pack_cfg(256, 4, 0), pack_cfg(128, 4, 16384), pack_cfg(512, 2, 0)},
+    /* decompress     */ {pack_cfg(256, 4, 0), pack_cfg(256, 2, 0), pack_cfg(256, 4, 49152)},
+    /* direct reduce  */ {pack_cfg(256, 1, 0), pack_cfg(512, 1, 0), pack_cfg(512, 2, 32768)},
 };
 inline LaunchConfig cfg_of(int kind, int mode)
 {
@@ -533,7 +534,8 @@ bool config_ok(int kind, int mode, const LaunchConfig &c)
         const int tile_vecs = kTile * (mode == PIPESGD_NONE ? 4 : mode == PIPESGD_TRUNC16 ? 2 : 1) / 16;
         return unit_quads <= tile_vecs;
     }
-    const bool needs_range = mode == PIPESGD_QUANT8 && (kind == kFirstSend || kind == kReduceScatter || kind == kFused || kind == kCompress);
+    const bool needs_range = mode == PIPESGD_QUANT8 && (kind == kFirstSend || kind == kReduceScatter || kind == kFused ||
+                                                        kind == kCompress || kind == kDirectReduce);
     return !needs_range || unit_quads == kTileQuads;
 }
 
@@ -1048,7 +1050,7 @@ static int direct_impl(int mode, const RingArgs &ra, const BucketTable &bt, uint
         rd.in[r] = p > 1 ? st.stage[r] : nullptr;
         rd.in_sc[r] = p > 1 ? st.stage_sc[r] : nullptr;
     }
-    const LaunchConfig c2 = cfg_of(kFused, mode);
+    const LaunchConfig c2 = cfg_of(kDirectReduce, mode);
 #define CALL(M) return launch_direct_reduce<M>(c2, rd, bt, slots, s);
     PIPESGD_MODE_SWITCH(mode, CALL)
 #undef CALL

@@ -432,7 +432,8 @@ def test_scaled_resnet_bucketed_pipeline(orc, mode, schedule):
 # ------------------------------------------------- every launch geometry --
 
 GEOS = [(64, 4), (128, 2), (128, 4), (256, 1), (256, 2), (256, 4), (512, 1), (512, 2), (1024, 1)]
-KINDS = [B.K_FIRST_SEND, B.K_REDUCE_SCATTER, B.K_ALLGATHER, B.K_FUSED, B.K_UPDATE, B.K_COMPRESS, B.K_DECOMPRESS]
+KINDS = [B.K_FIRST_SEND, B.K_REDUCE_SCATTER, B.K_ALLGATHER, B.K_FUSED, B.K_UPDATE, B.K_COMPRESS, B.K_DECOMPRESS,
+         B.K_DIRECT_REDUCE]
 
 
 @pytest.fixture
@@ -473,6 +474,20 @@ def test_every_launch_geometry_gives_the_same_bits(orc, restore_launch_configs, 
             assert_bits_equal(down(slots[r], mode), want[r][0], f"payload r={r} schedule={schedule}")
             if mode == B.QUANT8:
                 assert_bits_equal(down(scs[r]), want[r][1], f"scales r={r}")
+    # the one-exchange schedule (its owner-side kernel has a geometry entry of its own), per bucket as the ring
+    want_d = [np.zeros(N, dtype=orc.payload_dtype(mode)) for _ in range(p)]
+    for (st, nb) in buckets:
+        res = orc.allreduce_direct(mode, [g[st:st + nb] for g in packed])
+        for r in range(p):
+            want_d[r][st:st + nb] = res[r][0]
+    g_dev, slots, scs = ring_buffers(mode, packed, poison=False)
+    stage = [pay_buf(mode, N) for _ in range(p)]
+    stage_sc = [dev_zeros(B.num_scales(mode, N)) for _ in range(p)]
+    B.allreduce_direct(B.make_ring(mode, N, g_dev, slots, scs if mode == B.QUANT8 else None, buckets),
+                       B.make_workspace(stage, stage_sc if mode == B.QUANT8 else None))
+    sync()
+    for r in range(p):
+        assert_bits_equal(down(slots[r], mode), want_d[r], f"one-exchange payload r={r}")
     # codec + update on a flat ragged vector
     n = 4096 * 3 + 1234
     x = special_values(n, 99)
