@@ -58,6 +58,7 @@ def oracle_allreduce(orc, schedule, mode, grads, buckets):
     (3, B.TRUNC16, B.STEPWISE, 2),     # the headline configuration as bench.py times it: the two-stream runtime
     (3, B.TRUNC16, B.STEPWISE, 1),     # and back to back on one stream
     (3, B.TRUNC16, B.FUSED, 1),
+    (3, B.TRUNC16, B.FUSED, 2),        # bench.py --schedule fused also defaults to the two-stream runtime
     (4, B.QUANT8, B.STEPWISE, 2),
     (4, B.QUANT8, B.STEPWISE, 1),
     (4, B.QUANT8, B.FUSED, 1),

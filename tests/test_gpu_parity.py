@@ -661,8 +661,9 @@ def test_allreduce_pipelined_rejects_bad_arguments():
 # ------------------------------------------ Algorithm 1's two-thread runtime --
 
 @pytest.mark.parametrize("mode", MODES)
-@pytest.mark.parametrize("width", [1, 2, 3, 5])
-def test_two_stream_runtime_matches_oracle(orc, mode, width):
+@pytest.mark.parametrize("width,schedule", [(1, B.STEPWISE), (2, B.STEPWISE), (3, B.STEPWISE), (5, B.STEPWISE),
+                                            (1, B.FUSED), (2, B.FUSED)])
+def test_two_stream_runtime_matches_oracle(orc, mode, width, schedule):
     p, n, lr, m, iters = 4, 4096 * 11 + 77, 0.01, 0.9, 5 if width <= 2 else 9
     grad_fn = lambda r, w, t: W.gaussian(n, 1e-3, 21, (mode, r, t, 0))
     w0 = W.gaussian(n, 0.05, 23)
@@ -676,7 +677,7 @@ def test_two_stream_runtime_matches_oracle(orc, mode, width):
         sim.set_gradients([grad_fn(r, None, t) for r in range(p)])
         sync()
         cur = t % K
-        rt.iteration(sim.rings[cur], sim.updates[(cur + 1) % K], sim.updates[cur], B.STEPWISE, width, lr, m, 1.0,
+        rt.iteration(sim.rings[cur], sim.updates[(cur + 1) % K], sim.updates[cur], schedule, width, lr, m, 1.0,
                      compute_us=150.0, compute_workgroups=8, time_update=(t % 2 == 1))
     rt.sync()
     total_ms, timed = rt.update_time()                   # every other update launch was bracketed by timing events
