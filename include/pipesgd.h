@@ -12,10 +12,13 @@
  *     throws, aborts or logs.  Arguments are checked before the first launch:
  *     on any error other than PIPESGD_ERR_HIP nothing has been enqueued.
  *   - "DEVICE" pointers are HIP device memory owned by the caller; the library
- *     allocates no device memory.  The only state it keeps is on the host: the
- *     launch-geometry table (see "tuning") and what the opaque pipesgd_overlap
- *     and pipesgd_runtime objects hold (HIP events, two streams).  "HOST"
- *     pointers are ordinary host memory read during the call only.
+ *     allocates no device memory at run time.  The only device memory of its
+ *     own is the fixed array of PIPESGD_STATIC_SCRATCH_BYTES inside its code
+ *     object, used by pipesgd_allreduce_direct_static alone.  The state it
+ *     keeps on the host: the launch-geometry table (see "tuning"), that array's
+ *     address per device, and what the opaque pipesgd_overlap and
+ *     pipesgd_runtime objects hold (HIP events, two streams).  "HOST" pointers
+ *     are ordinary host memory read during the call only.
  *   - Every DEVICE pointer must be 16-byte aligned.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Calls enqueue work on it and return without synchronising.  Calls on
