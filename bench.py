@@ -34,7 +34,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 MODE_OF_CONFIG = {1: 0, 2: 0, 3: 1, 4: 2, 5: 1}
 
 
-from paper_1811_03619_amd.studies import bytes_model, payload_bytes_per_elem  # noqa: E402  (the byte accounting)
+from bench_studies import bytes_model, payload_bytes_per_elem  # noqa: E402  (the byte accounting)
 
 
 INFINITY_CACHE_BYTES = 256 * 2 ** 20   # MI355X memory-side cache
@@ -342,7 +342,7 @@ def main() -> int:
 
     study = None
     if args.study is not None:
-        from paper_1811_03619_amd import studies
+        import bench_studies as studies
         if args.study == "within-allreduce":
             study = studies.within_allreduce(sim, mode, n, p)
         elif args.study == "two-thread-runtime":

@@ -60,9 +60,9 @@ def within_allreduce(sim, mode, n, p, reps: int = 15):
     import numpy as np
     import torch
 
-    from . import binding as B
+    from paper_1811_03619_amd import binding as B
 
-    from .pipeline import payload_empty
+    from paper_1811_03619_amd.pipeline import payload_empty
     dev = sim.device
     ns = B.num_scales(mode, n)
     recv = [payload_empty(mode, n, dev) for _ in range(p)]
@@ -131,9 +131,9 @@ def size_sweep(mode, p, momentum, seed, reps: int = 20, stagger: bool = True):
     import numpy as np
     import torch
 
-    from . import binding as B
+    from paper_1811_03619_amd import binding as B
 
-    from .pipeline import PipeSgdSim
+    from paper_1811_03619_amd.pipeline import PipeSgdSim
     rows = []
     for m in (1 << 16, 1 << 18, 1 << 20, 1 << 22, 1 << 24, 1 << 25, 1 << 26, 1 << 27, 1 << 28):
         sim = PipeSgdSim(mode, p, m, 0.01, momentum, stagger=stagger)
@@ -171,9 +171,9 @@ def ring_cost_model(mode, n, p, seed, reps: int = 30):
     import numpy as np
     import torch
 
-    from . import binding as B
+    from paper_1811_03619_amd import binding as B
 
-    from .pipeline import PipeSgdSim
+    from paper_1811_03619_amd.pipeline import PipeSgdSim
 
     def rounds_ms(m):
         sim = PipeSgdSim(mode, p, m, 0.01, 0.9)
@@ -229,7 +229,7 @@ def two_thread_runtime(sim, schedule, iters: int = 30):
     import numpy as np
     import torch
 
-    from . import binding as B
+    from paper_1811_03619_amd import binding as B
 
     rt = B.Runtime()
     p = sim.p
@@ -248,7 +248,7 @@ def two_thread_runtime(sim, schedule, iters: int = 30):
     l_comm = alone(lambda: B.allreduce_sim(sim.rings[0], schedule))
 
     # a third result-slot set for the width-3 leg (Alg. 1 keeps K of them)
-    from .pipeline import payload_empty
+    from paper_1811_03619_amd.pipeline import payload_empty
     ns = B.num_scales(sim.mode, sim.n)
     slots3 = [payload_empty(sim.mode, sim.n, sim.device) for _ in range(p)]
     scales3 = [torch.zeros(max(ns, 1), dtype=torch.float32, device=sim.device)[:ns] for _ in range(p)]
