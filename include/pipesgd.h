@@ -411,7 +411,8 @@ int pipesgd_unpack(const pipesgd_segment *segments, uint64_t num, uint64_t total
  * The caller keeps K slot sets (two for width 1 and 2) and rotates them: `ring`
  * writes the slot set of iteration t, `stale_*` name the slot set of iteration
  * t-(K-1) (an all-zero set while t < K), `fresh_*` the set `ring` writes (width
- * 1 only).
+ * 1 only).  With width >= 2 the stale set must not be the set `ring` writes
+ * (PIPESGD_ERR_ARG): the two streams would race on it.
  * The caller must not change g_local while an AllReduce that reads it may still
  * be running (pipesgd_runtime_sync, or double-buffer the gradients).
  * pipesgd_runtime_iteration checks every field (the ring, the slot / w / v tables

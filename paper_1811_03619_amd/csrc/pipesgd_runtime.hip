@@ -137,6 +137,13 @@ int pipesgd_runtime_iteration(pipesgd_runtime *rt, const pipesgd_runtime_iter *i
                                            sync ? it->fresh_scales : it->stale_scales, it->ring->n, it->w, it->v,
                                            it->momentum);
     }
+    if (rc == PIPESGD_OK && it->width >= 2 && it->ring->n > 0) {
+        // the update reads the stale slot set while the AllReduce on the other stream writes the ring's: they
+        // must be different buffers (pointer identity; partial overlaps are the caller's to avoid)
+        for (int r = 0; r < it->replicas && rc == PIPESGD_OK; ++r)
+            for (int q = 0; q < it->ring->workers; ++q)
+                if (it->stale_g_sum_c[r] == it->ring->g_sum_c[q]) { rc = PIPESGD_ERR_ARG; break; }
+    }
     if (rc == PIPESGD_OK) rc = pipesgd_internal_check_standin(it->compute_us, wg);
     if (rc == PIPESGD_OK) rc = pipesgd_internal_check_standin(it->wire_us, 1);
     if (rc != PIPESGD_OK) return rc;

@@ -769,6 +769,8 @@ def test_runtime_rejected_call_enqueues_nothing_and_the_runtime_goes_on(orc, wid
         (lambda it: setattr(it, "schedule", 7), -3),
         (lambda it: setattr(it, "flags", 2), -1),
     ]
+    if width >= 2:      # the stale slot set may not be the one the AllReduce writes: the two streams would race
+        mutations.append((lambda it: setattr(it, "stale_g_sum_c", it.fresh_g_sum_c), -1))
     for t in range(1, iters + 1):
         rt.sync()
         sim.set_gradients([grad_fn(r, None, t) for r in range(p)])
