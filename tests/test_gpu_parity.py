@@ -1187,6 +1187,44 @@ def test_random_shapes_all_schedules(orc, case):
             assert_bits_equal(down(slots2[r], mode), want_hd[r][0], f"payload r={r} halving-doubling")
             if mode == B.QUANT8 and not buckets:
                 assert_bits_equal(down(scs2[r]), want_hd[r][1], f"scales r={r} halving-doubling")
+    # the one-exchange schedule through both of its entry points (the second keeps its send buffers in the
+    # library's static device array), each bucket against the oracle's one-exchange branch
+    if buckets:
+        want_d = [[np.zeros(n, dtype=orc.payload_dtype(mode)), None] for _ in range(p)]
+        for (st, nb) in buckets:
+            res = orc.allreduce_direct(mode, [g[st:st + nb] for g in grads])
+            for r in range(p):
+                want_d[r][0][st:st + nb] = res[r][0]
+    else:
+        want_d = orc.allreduce_direct(mode, grads)
+    for static in (False, True):
+        g_dev3, slots3, scs3 = ring_buffers(mode, grads, poison=not buckets)
+        ring3 = B.make_ring(mode, n, g_dev3, slots3, scs3 if mode == B.QUANT8 else None, buckets)
+        if static:
+            B.allreduce_direct_static(ring3)
+        else:
+            stage3 = [pay_buf(mode, n) for _ in range(p)]
+            stage_sc3 = [dev_zeros(B.num_scales(mode, n), fill=-2.0) for _ in range(p)]
+            B.allreduce_direct(ring3, B.make_workspace(stage3, stage_sc3 if mode == B.QUANT8 else None))
+        sync()
+        for r in range(p):
+            assert_bits_equal(down(slots3[r], mode), want_d[r][0], f"payload r={r} one-exchange static={static}")
+            if mode == B.QUANT8 and not buckets:
+                assert_bits_equal(down(scs3[r]), want_d[r][1], f"scales r={r} one-exchange static={static}")
+    # the pipelined schedule (a random number of sub-blocks, two streams) gives the ring's bits
+    g_dev4, slots4, scs4 = ring_buffers(mode, grads, poison=not buckets)
+    recv4 = [pay_buf(mode, n) for _ in range(p)]
+    recv_sc4 = [dev_zeros(B.num_scales(mode, n), fill=-2.0) for _ in range(p)]
+    ov, rt4 = B.Overlap(), B.Runtime()
+    B.allreduce_pipelined(B.make_ring(mode, n, g_dev4, slots4, scs4 if mode == B.QUANT8 else None, buckets),
+                          B.make_workspace(recv4, recv_sc4 if mode == B.QUANT8 else None), int(rng.integers(1, 9)), ov,
+                          rt4.stream(0), rt4.stream(1))
+    rt4.sync()
+    sync()
+    for r in range(p):
+        assert_bits_equal(down(slots4[r], mode), want[r][0], f"payload r={r} pipelined")
+    ov.close()
+    rt4.close()
     # update of all replicas from the result
     lr, m = float(rng.choice([0.01, 0.1])), float(rng.choice([0.0, 0.9]))
     w0 = [W.gaussian(n, 1.0, 7 + case, (r, 1, 0, 0)) for r in range(p)]
